@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the CurDKV selection path on one MI355X.
+
+A step is one pass of the whole hot path -- curdkv_scores, curdkv_select,
+curdkv_compact back to back on one stream -- over a synthetic Llama-3-8B-shaped
+cache (32 layers x 8 KV heads x 32768 tokens x d=128, bf16, r=64) that is already
+resident in HBM.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--keep 0.10]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+
+
+def algorithmic_bytes(cfg, budgets, esize=2):
+    """Bytes the method has to move (per step and per part).  Per head: read K and
+    V once (2*n*d*e), write the scores (4n); select reads them (4n) and writes
+    indices (4k); compact reads indices (4k), reads and writes k rows of K and V."""
+    heads, n, d = cfg.layers * cfg.kv_heads, cfg.n, cfg.d
+    ksum = int(np.sum(budgets.astype(np.int64)))
+    row = d * esize
+    scan = heads * n * (2 * row)
+    scores_call = scan + heads * n * 4
+    select_call = heads * n * 4 + ksum * 4
+    compact_call = ksum * (4 + 4 * row)
+    return dict(scan=scan, scores=scores_call, select=select_call, compact=compact_call,
+                total=scores_call + select_call + compact_call)
+
+
+def cpu_baseline(cfg, Kd, Vd, budgets, n_sink, max_seconds=25.0):
+    """The CPU oracle, as it stands, on the same workload: groups in (layer, head)
+    order, for as many as fit in the time budget (copies from the GPU not timed)."""
+    import torch
+    from oracle import curdkv_oracle as orc
+
+    def to_host(t):
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    H, n = cfg.kv_heads, cfg.n
+    done, t_used = 0, 0.0
+    for i in range(cfg.layers * H):
+        l, h = divmod(i, H)
+        K, V = to_host(Kd[l, h]), to_host(Vd[l, h])
+        t0 = time.perf_counter()
+        G = orc.sketch(cfg.sketch_seed, l, h, H, cfg.d, cfg.r, cfg.dtype)
+        orc.compress_group(K, V, cfg.dtype, G, int(budgets[l * H + h]), n_sink)
+        t_used += time.perf_counter() - t0
+        done += 1
+        if t_used > max_seconds:
+            break
+    return {"value": done * n / t_used, "unit": "KV tokens/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"the first {done} of {cfg.layers * H} (layer, head) groups of {n} tokens, "
+                      f"{t_used:.1f} s of float64 numpy, single process"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--keep", type=float, default=None, help="keep fraction (default: the config's first)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (every (layer, head) is independent; "
+              "there is nothing to exchange).  Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_15038_amd import binding as B, workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    B.lib()
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.config]
+    keep = cfg.keep[0] if args.keep is None else args.keep
+    budgets = wl.budgets_for(cfg, keep)
+    offsets = wl.offsets_for(budgets)
+    total = int(offsets[-1])
+    L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
+    heads = L * H
+
+    Kd, Vd = wl.device_cache(cfg)
+    scores = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+    indices = torch.empty((max(total, 1),), dtype=torch.int32, device="cuda")
+    Ko = torch.empty((max(total, 1), d), dtype=torch.bfloat16, device="cuda")
+    Vo = torch.empty((max(total, 1), d), dtype=torch.bfloat16, device="cuda")
+    ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed)
+    s = cfg.n_sink
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        ctx.scores(Kd, Vd, n, scores)
+        if ev:
+            ev[1].record()
+        ctx.select(scores, n, budgets, s, offsets, indices)
+        if ev:
+            ev[2].record()
+        ctx.compact(Kd, Vd, n, indices, offsets, Ko, Vo)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    part_ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
+    step_ms_events = np.array([e[0].elapsed_time(e[3]) for e in evs])
+    avg = part_ms.mean(0)
+
+    ab = algorithmic_bytes(cfg, budgets)
+    kv_tokens = heads * n
+    value = kv_tokens / (ms_per_step * 1e-3)
+    scores_gbs = ab["scores"] / (avg[0] * 1e-3) / 1e9
+    out = {
+        "metric": "KV tokens scored+compacted/sec at 8B shape, 32k ctx; % of HBM peak",
+        "value": value, "unit": "KV tokens/s (one token of one layer and KV head)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} layers x {H} KV heads (GQA group {cfg.group}), "
+                               f"n={n}, d={d}, r={cfg.r}, keep={keep:g} (k/head mean "
+                               f"{total / heads:.0f}), sinks={s}, bf16, resident in HBM",
+                   "layers": L, "kv_heads": H, "n": n, "d": d, "r": cfg.r, "keep": keep},
+        "context_tokens_per_s": n / (ms_per_step * 1e-3),
+        "path_GBps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
+        "path_frac_of_hbm_peak": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "ms_events": {"step_median": float(np.median(step_ms_events)),
+                      "scores": float(avg[0]), "select": float(avg[1]), "compact": float(avg[2])},
+        "GBps": {"scores": scores_gbs, "select": ab["select"] / (avg[1] * 1e-3) / 1e9,
+                 "compact": ab["compact"] / (avg[2] * 1e-3) / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "curdkv_scores (project + row-norm^2 + combine + normalise)",
+                     "achieved": scores_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": scores_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": ab["scores"], "avg_ms": float(avg[0])},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, Kd.view(L, H, n, d), Vd.view(L, H, n, d), budgets, s)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

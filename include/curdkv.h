@@ -1,0 +1,136 @@
+/*
+ * curdkv.h -- C ABI of the CurDKV post-prefill KV selection library for
+ * AMD MI355X (gfx950).
+ *
+ * The library computes Algorithm 1 of "Value-Guided KV Compression for LLMs via
+ * Approximated CUR Decomposition" (CurDKV) for every layer and KV group of a
+ * GQA cache: sketch, project, row-norm squared, combine, normalise, keep sinks
+ * plus top-k, gather.  All arithmetic runs in HIP kernels; there is no CPU
+ * fallback.  Layers are an outer batch dimension over the algorithm's group
+ * loop; a batch of sequences folds into `layers`.
+ *
+ * Conventions
+ *   - Every function returns CURDKV_OK (0) or a negative error code and never
+ *     throws.  Arguments are validated on the host before anything is launched;
+ *     on error nothing has been launched.
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     neither frees nor keeps them.  "host" pointers are ordinary host memory,
+ *     read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
+ *     three compute calls only enqueue work on it and do not synchronise.
+ *   - The context owns the sketches, the per-block partial sums and the device
+ *     copy of the offsets.  Calls on one context must not overlap in time on
+ *     different streams.
+ *   - K and V are row-major [layers, kv_heads, n, head_dim] in the context's
+ *     storage type; token j of group (l, h) starts at element
+ *     ((l*kv_heads + h)*n + j)*head_dim.  Base pointers must be 16-byte aligned.
+ */
+#ifndef CURDKV_H
+#define CURDKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CURDKV_OK               0
+#define CURDKV_ERR_INVALID_ARG -1   /* null pointer, size out of range, inconsistent offsets */
+#define CURDKV_ERR_UNSUPPORTED -2   /* head_dim, sketch_dim or dtype the kernels do not cover */
+#define CURDKV_ERR_HIP         -3   /* a HIP runtime call failed (no device, launch error, ...) */
+#define CURDKV_ERR_OOM         -4   /* device or host allocation failed */
+
+#define CURDKV_DTYPE_F32  0
+#define CURDKV_DTYPE_BF16 1
+
+typedef struct curdkv_ctx curdkv_ctx;
+
+/* Problem statement of Algorithm 1 (inputs K, V in R^{g x n x d}, projection
+ * dimension r) extended over layers.  group_size (query heads per KV group)
+ * is carried for curdkv_fold; the scores themselves depend on K and V only. */
+typedef struct curdkv_config {
+    int32_t  layers;       /* >= 1 */
+    int32_t  kv_heads;     /* g, number of KV groups per layer, >= 1 */
+    int32_t  group_size;   /* query heads per KV group, >= 1 */
+    int32_t  head_dim;     /* d; supported: 128 */
+    int32_t  sketch_dim;   /* r in [1, 128]; padded internally with zero columns */
+    int32_t  dtype;        /* CURDKV_DTYPE_* : storage type of K, V and of G */
+    int64_t  max_tokens;   /* largest n any call will pass, >= 1 */
+    uint64_t seed;         /* seed of the sketch generator */
+} curdkv_config;
+
+/* Create a context on the current HIP device: generates the sketch G of every
+ * (layer, group) on the host, uploads it in the kernels' operand layout and
+ * allocates the reduction workspace.  Synchronous.  *out is set only on success. */
+int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg);
+
+/* Free everything the context owns.  Synchronises the device first.  NULL is accepted. */
+int curdkv_destroy(curdkv_ctx* ctx);
+
+/* Host-only (no GPU needed): write G of group (layer, head) to G_host[d*r],
+ * row-major [head_dim, sketch_dim], as float.
+ *
+ * Algorithm 1, "Sample Gaussian matrix G in R^{d x r} with G_ij ~ N(0, 1/r)";
+ * one G per (layer, group), shared by K and V.  The paper fixes no generator:
+ * element (i, j) has counter c = ((layer*kv_heads + head)*d + i)*r + j and
+ * takes SplitMix64 outputs number 2c+1 and 2c+2 (w1, w2) of the stream started
+ * at `seed`; u1 = ((w1>>11)+1)*2^-53, u2 = (w2>>11)*2^-53,
+ * G_ij = sqrt(-2 ln u1) cos(2 pi u2) / sqrt(r) in double, then rounded to the
+ * storage type (nearest even).  The rounded value is what the kernels use. */
+int curdkv_sketch_host(const curdkv_config* cfg, int32_t layer, int32_t head, float* G_host);
+
+/* Replace the sketch of one group by caller-supplied values (host, row-major
+ * [head_dim, sketch_dim] floats; rounded to the storage type).  Synchronous.
+ * For callers that draw G themselves, as Algorithm 1 literally does. */
+int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float* G_host);
+
+/* Algorithm 1, lines "Project" to "Normalize": for every (layer, group)
+ *   lK_j = ||(K G)[j]||^2,  lV_j = ||(V G)[j]||^2,  lKV_j = lK_j * lV_j,
+ *   scores_j = lKV_j / sum_j lKV_j   (sum over all n rows; 1/n if the sum is 0).
+ * K, V: device, [layers, kv_heads, n, head_dim], storage type, read once.
+ * scores: device float [layers, kv_heads, n], written.
+ * Products accumulate in fp32; lKV must stay inside the fp32 range.
+ * 1 <= n <= max_tokens. */
+int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                  float* scores, void* stream);
+
+/* GQA score fold (Section 2, GQA-compatible eviction; Section 3.2 assumes a
+ * group of query heads shares one K_i, V_i): mean over the group of per-query-
+ * head scores.  scores_q: device float [layers, kv_heads, group_size, n];
+ * scores: device float [layers, kv_heads, n].  CurDKV's own scores are already
+ * per group, so the hot path does not need this call; it serves score sources
+ * that are per query head.  Summation order is fixed (head 0 first). */
+int curdkv_fold(curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores,
+                void* stream);
+
+/* Algorithm 1, lines "Preserve first s tokens", "Select top-(k-s)" and
+ * "Combine": S = {0..s-1} U (TopK(scores[s:], k-s) + s) for every (layer, group).
+ * scores: device float [layers, kv_heads, n], non-negative, no NaN.
+ * budgets: host int32 [layers*kv_heads], k per group (sinks included), 0 <= k <= n.
+ * offsets: host int64 [layers*kv_heads + 1], offsets[0] = 0 and
+ *          offsets[i+1] = offsets[i] + budgets[i].
+ * indices: device int32 [offsets[last]]; group i's tokens go to
+ *          indices[offsets[i] .. offsets[i+1]) in ascending token order.
+ * Ties: larger score first, then smaller token index.  k <= s keeps tokens
+ * 0..k-1.  n_sink >= 0. */
+int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n,
+                  const int32_t* budgets, int32_t n_sink, const int64_t* offsets,
+                  int32_t* indices, void* stream);
+
+/* Algorithm 1, last line: K' = K[S], V' = V[S] (rows of the original cache).
+ * indices, offsets: as written by / passed to curdkv_select (offsets on host;
+ * non-decreasing, offsets[0] = 0, each group's count <= n; every index must lie
+ * in [0, n)).
+ * K_out, V_out: device, packed [offsets[last], head_dim], storage type; equal to
+ * [layers, kv_heads, k, head_dim] when all budgets are k.  Bit-exact copies. */
+int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                   const int32_t* indices, const int64_t* offsets,
+                   void* K_out, void* V_out, void* stream);
+
+/* Text for an error code; never NULL. */
+const char* curdkv_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CURDKV_H */

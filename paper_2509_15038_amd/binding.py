@@ -1,0 +1,171 @@
+"""ctypes binding of libcurdkv.so: the same entry points as include/curdkv.h,
+argument marshalling only.  Every step of the path runs in the HIP kernels.
+
+torch appears here only as the owner of device memory and streams: tensors are
+passed as raw pointers.  If the compiled library is missing the import of any
+entry point fails loudly; there is no fallback.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcurdkv.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_OOM = 0, -1, -2, -3, -4
+DTYPE_F32, DTYPE_BF16 = 0, 1
+_DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
+
+EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
+           "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_strerror"]
+
+
+class CurdkvConfig(C.Structure):
+    _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("group_size", C.c_int32),
+                ("head_dim", C.c_int32), ("sketch_dim", C.c_int32), ("dtype", C.c_int32),
+                ("max_tokens", C.c_int64), ("seed", C.c_uint64)]
+
+
+class CurdkvError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2509_15038_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    cfgp = C.POINTER(CurdkvConfig)
+    L.curdkv_create.argtypes = [C.POINTER(vp), cfgp]
+    L.curdkv_destroy.argtypes = [vp]
+    L.curdkv_sketch_host.argtypes = [cfgp, i32, i32, vp]
+    L.curdkv_set_sketch.argtypes = [vp, i32, i32, vp]
+    L.curdkv_scores.argtypes = [vp, vp, vp, i64, vp, vp]
+    L.curdkv_fold.argtypes = [vp, vp, i64, vp, vp]
+    L.curdkv_select.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
+    L.curdkv_compact.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
+    L.curdkv_strerror.argtypes = [C.c_int]
+    L.curdkv_strerror.restype = C.c_char_p
+    for name in EXPORTS[:-1]:
+        getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return lib().curdkv_strerror(int(code)).decode()
+
+
+def make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed):
+    return CurdkvConfig(int(layers), int(kv_heads), int(group_size), int(head_dim),
+                        int(sketch_dim), _DTYPES[dtype] if isinstance(dtype, str) else int(dtype),
+                        int(max_tokens), int(seed) & 0xFFFFFFFFFFFFFFFF)
+
+
+def curdkv_sketch_host(cfg: CurdkvConfig, layer: int, head: int) -> np.ndarray:
+    """G of one (layer, head) as float32 [head_dim, sketch_dim]; host only, no GPU."""
+    out = np.empty((cfg.head_dim, cfg.sketch_dim), dtype=np.float32)
+    rc = lib().curdkv_sketch_host(C.byref(cfg), layer, head, out.ctypes.data)
+    if rc != OK:
+        raise CurdkvError(rc, "curdkv_sketch_host")
+    return out
+
+
+def _ptr(t) -> int:
+    """Device (torch) or host (numpy) buffer -> address; None -> NULL."""
+    if t is None:
+        return 0
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Context:
+    """Owns one curdkv_ctx.  Methods mirror the C entry points and return the raw
+    status code through CurdkvError on failure."""
+
+    def __init__(self, layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed):
+        self.cfg = make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype,
+                               max_tokens, seed)
+        self._h = C.c_void_p()
+        rc = lib().curdkv_create(C.byref(self._h), C.byref(self.cfg))
+        if rc != OK:
+            self._h = C.c_void_p()
+            raise CurdkvError(rc, "curdkv_create")
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib().curdkv_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    @property
+    def heads(self) -> int:
+        return self.cfg.layers * self.cfg.kv_heads
+
+    def set_sketch(self, layer: int, head: int, G: np.ndarray):
+        G = np.ascontiguousarray(G, dtype=np.float32)
+        assert G.shape == (self.cfg.head_dim, self.cfg.sketch_dim)
+        rc = lib().curdkv_set_sketch(self._h, layer, head, G.ctypes.data)
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_set_sketch")
+
+    def scores(self, K, V, n: int, scores, stream=None):
+        rc = lib().curdkv_scores(self._h, _ptr(K), _ptr(V), int(n), _ptr(scores), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_scores")
+
+    def fold(self, scores_q, n: int, scores, stream=None):
+        rc = lib().curdkv_fold(self._h, _ptr(scores_q), int(n), _ptr(scores), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_fold")
+
+    def select(self, scores, n: int, budgets: np.ndarray, n_sink: int, offsets: np.ndarray,
+               indices, stream=None):
+        assert budgets.dtype == np.int32 and offsets.dtype == np.int64
+        assert budgets.size == self.heads and offsets.size == self.heads + 1
+        rc = lib().curdkv_select(self._h, _ptr(scores), int(n), budgets.ctypes.data, int(n_sink),
+                                 offsets.ctypes.data, _ptr(indices), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_select")
+
+    def compact(self, K, V, n: int, indices, offsets: np.ndarray, K_out, V_out, stream=None):
+        assert offsets.dtype == np.int64 and offsets.size == self.heads + 1
+        rc = lib().curdkv_compact(self._h, _ptr(K), _ptr(V), int(n), _ptr(indices),
+                                  offsets.ctypes.data, _ptr(K_out), _ptr(V_out), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_compact")

@@ -1,0 +1,235 @@
+// Host side of the C ABI: argument checks, context lifetime, offsets upload,
+// kernel launches.  No arithmetic of the method happens here except the
+// generation of the sketch (sketch_host.cpp), which is an input of the kernels.
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "curdkv_internal.h"
+
+using namespace curdkv;
+
+namespace {
+
+int padded_col_blocks(int r) {
+    if (r <= 32) return 1;
+    if (r <= 64) return 2;
+    return 4;
+}
+
+int check_config(const curdkv_config* cfg) {
+    if (!cfg) return CURDKV_ERR_INVALID_ARG;
+    if (cfg->layers < 1 || cfg->kv_heads < 1 || cfg->group_size < 1 || cfg->max_tokens < 1)
+        return CURDKV_ERR_INVALID_ARG;
+    if ((int64_t)cfg->layers * cfg->kv_heads > (1 << 24)) return CURDKV_ERR_INVALID_ARG;
+    if (cfg->sketch_dim < 1) return CURDKV_ERR_INVALID_ARG;
+    if (cfg->dtype != CURDKV_DTYPE_F32 && cfg->dtype != CURDKV_DTYPE_BF16) return CURDKV_ERR_UNSUPPORTED;
+    if (cfg->head_dim != kHeadDim) return CURDKV_ERR_UNSUPPORTED;
+    if (cfg->sketch_dim > kColBlock * kMaxColBlocks) return CURDKV_ERR_UNSUPPORTED;
+    if (cfg->max_tokens > 0x7FFFFFFFLL) return CURDKV_ERR_UNSUPPORTED;   // indices are int32
+    return CURDKV_OK;
+}
+
+size_t storage_bytes(int dtype) { return dtype == CURDKV_DTYPE_BF16 ? 2 : 4; }
+
+// Checks offsets (host) and makes the device copy current on `stream`.
+int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets, int64_t n,
+                 hipStream_t stream, int64_t* total) {
+    const int heads = ctx->heads;
+    if (offsets[0] != 0) return CURDKV_ERR_INVALID_ARG;
+    for (int i = 0; i < heads; ++i) {
+        const int64_t k = offsets[i + 1] - offsets[i];
+        if (k < 0 || k > n) return CURDKV_ERR_INVALID_ARG;
+        if (budgets && (int64_t)budgets[i] != k) return CURDKV_ERR_INVALID_ARG;
+    }
+    *total = offsets[heads];
+    Plan& pl = ctx->plan;
+    const size_t bytes = (size_t)(heads + 1) * sizeof(int64_t);
+    if (pl.valid && std::memcmp(pl.cached.data(), offsets, bytes) == 0) return CURDKV_OK;
+    if (pl.copy_pending) {                       // staging buffer may still be being read
+        if (hipEventSynchronize(pl.copied) != hipSuccess) return CURDKV_ERR_HIP;
+        pl.copy_pending = false;
+    }
+    std::memcpy(pl.h_staging, offsets, bytes);
+    pl.valid = false;
+    if (hipMemcpyAsync(pl.d_offsets, pl.h_staging, bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
+        return CURDKV_ERR_HIP;
+    if (hipEventRecord(pl.copied, stream) != hipSuccess) return CURDKV_ERR_HIP;
+    pl.copy_pending = true;
+    std::memcpy(pl.cached.data(), offsets, bytes);
+    pl.valid = true;
+    return CURDKV_OK;
+}
+
+void release(curdkv_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->d_G) (void)hipFree(ctx->d_G);
+    if (ctx->d_partial) (void)hipFree(ctx->d_partial);
+    if (ctx->plan.d_offsets) (void)hipFree(ctx->plan.d_offsets);
+    if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
+    if (ctx->plan.copied) (void)hipEventDestroy(ctx->plan.copied);
+    delete ctx;
+}
+
+int upload_sketch(curdkv_ctx* ctx, int group, const float* G_rounded) {
+    const size_t elems = ctx->g_elems_per_head;
+    const size_t bytes = elems * storage_bytes(ctx->cfg.dtype);
+    void* packed = std::malloc(bytes);
+    if (!packed) return CURDKV_ERR_OOM;
+    pack_sketch(ctx->cfg, ctx->col_blocks, G_rounded, packed);
+    hipError_t e = hipMemcpy(static_cast<char*>(ctx->d_G) + (size_t)group * bytes, packed, bytes,
+                             hipMemcpyHostToDevice);
+    std::free(packed);
+    return e == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* curdkv_strerror(int code) {
+    switch (code) {
+        case CURDKV_OK: return "ok";
+        case CURDKV_ERR_INVALID_ARG: return "invalid argument";
+        case CURDKV_ERR_UNSUPPORTED: return "unsupported head_dim, sketch_dim, dtype or size";
+        case CURDKV_ERR_HIP: return "HIP runtime error";
+        case CURDKV_ERR_OOM: return "out of memory";
+        default: return "unknown error code";
+    }
+}
+
+int curdkv_sketch_host(const curdkv_config* cfg, int32_t layer, int32_t head, float* G_host) {
+    const int rc = check_config(cfg);
+    if (rc != CURDKV_OK) return rc;
+    if (!G_host || layer < 0 || layer >= cfg->layers || head < 0 || head >= cfg->kv_heads)
+        return CURDKV_ERR_INVALID_ARG;
+    sketch_values(*cfg, layer, head, G_host);
+    return CURDKV_OK;
+}
+
+int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
+    if (!out) return CURDKV_ERR_INVALID_ARG;
+    const int rc = check_config(cfg);
+    if (rc != CURDKV_OK) return rc;
+    curdkv_ctx* ctx = new (std::nothrow) curdkv_ctx();
+    if (!ctx) return CURDKV_ERR_OOM;
+    ctx->cfg = *cfg;
+    ctx->heads = cfg->layers * cfg->kv_heads;
+    ctx->col_blocks = padded_col_blocks(cfg->sketch_dim);
+    ctx->g_elems_per_head = packed_elems(ctx->col_blocks);
+
+    int lds = 0, cus = 0;
+    if (hipGetDevice(&ctx->device) != hipSuccess ||
+        hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, ctx->device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device) != hipSuccess) {
+        release(ctx);
+        return CURDKV_ERR_HIP;
+    }
+    ctx->lds_limit = lds;
+    ctx->num_cu = cus > 0 ? cus : 256;
+
+    const size_t g_bytes = (size_t)ctx->heads * ctx->g_elems_per_head * storage_bytes(cfg->dtype);
+    const size_t off_bytes = (size_t)(ctx->heads + 1) * sizeof(int64_t);
+    if (hipMalloc(&ctx->d_G, g_bytes) != hipSuccess ||
+        hipMalloc((void**)&ctx->d_partial, (size_t)ctx->heads * kMaxBlocksPerHead * sizeof(float)) != hipSuccess ||
+        hipMalloc((void**)&ctx->plan.d_offsets, off_bytes) != hipSuccess ||
+        hipHostMalloc((void**)&ctx->plan.h_staging, off_bytes, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        release(ctx);
+        return CURDKV_ERR_OOM;
+    }
+    if (hipEventCreateWithFlags(&ctx->plan.copied, hipEventDisableTiming) != hipSuccess) {
+        release(ctx);
+        return CURDKV_ERR_HIP;
+    }
+    try {
+        ctx->plan.cached.assign((size_t)ctx->heads + 1, 0);
+    } catch (...) {
+        release(ctx);
+        return CURDKV_ERR_OOM;
+    }
+
+    float* G = static_cast<float*>(std::malloc((size_t)cfg->head_dim * cfg->sketch_dim * sizeof(float)));
+    if (!G) { release(ctx); return CURDKV_ERR_OOM; }
+    int err = CURDKV_OK;
+    for (int l = 0; l < cfg->layers && err == CURDKV_OK; ++l)
+        for (int h = 0; h < cfg->kv_heads && err == CURDKV_OK; ++h) {
+            sketch_values(*cfg, l, h, G);
+            err = upload_sketch(ctx, l * cfg->kv_heads + h, G);
+        }
+    std::free(G);
+    if (err == CURDKV_OK && (configure_kernels(ctx) != hipSuccess || configure_select(ctx) != hipSuccess))
+        err = CURDKV_ERR_HIP;
+    if (err != CURDKV_OK) { release(ctx); return err; }
+    *out = ctx;
+    return CURDKV_OK;
+}
+
+int curdkv_destroy(curdkv_ctx* ctx) {
+    if (!ctx) return CURDKV_OK;
+    const hipError_t e = hipDeviceSynchronize();
+    release(ctx);
+    return e == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float* G_host) {
+    if (!ctx || !G_host) return CURDKV_ERR_INVALID_ARG;
+    if (layer < 0 || layer >= ctx->cfg.layers || head < 0 || head >= ctx->cfg.kv_heads)
+        return CURDKV_ERR_INVALID_ARG;
+    const size_t count = (size_t)ctx->cfg.head_dim * ctx->cfg.sketch_dim;
+    float* G = static_cast<float*>(std::malloc(count * sizeof(float)));
+    if (!G) return CURDKV_ERR_OOM;
+    std::memcpy(G, G_host, count * sizeof(float));
+    round_to_storage(G, count, ctx->cfg.dtype);
+    if (hipDeviceSynchronize() != hipSuccess) { std::free(G); return CURDKV_ERR_HIP; }
+    const int rc = upload_sketch(ctx, layer * ctx->cfg.kv_heads + head, G);
+    std::free(G);
+    return rc;
+}
+
+int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, float* scores,
+                  void* stream) {
+    if (!ctx || !K || !V || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
+    if (((uintptr_t)K | (uintptr_t)V) & 15u) return CURDKV_ERR_INVALID_ARG;
+    return launch_scores(ctx, K, V, n, scores, (hipStream_t)stream) == hipSuccess ? CURDKV_OK
+                                                                                  : CURDKV_ERR_HIP;
+}
+
+int curdkv_fold(curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores, void* stream) {
+    if (!ctx || !scores_q || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
+    return launch_fold(ctx, scores_q, n, scores, (hipStream_t)stream) == hipSuccess ? CURDKV_OK
+                                                                                    : CURDKV_ERR_HIP;
+}
+
+int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n, const int32_t* budgets,
+                  int32_t n_sink, const int64_t* offsets, int32_t* indices, void* stream) {
+    if (!ctx || !scores || !budgets || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0) return CURDKV_ERR_INVALID_ARG;
+    int64_t total = 0;
+    const int rc = sync_offsets(ctx, offsets, budgets, n, (hipStream_t)stream, &total);
+    if (rc != CURDKV_OK) return rc;
+    if (total == 0) return CURDKV_OK;
+    if (!indices) return CURDKV_ERR_INVALID_ARG;
+    return launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, (hipStream_t)stream) == hipSuccess
+               ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, const int32_t* indices,
+                   const int64_t* offsets, void* K_out, void* V_out, void* stream) {
+    if (!ctx || !K || !V || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
+    if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)K_out | (uintptr_t)V_out) & 15u) return CURDKV_ERR_INVALID_ARG;
+    int64_t total = 0;
+    const int rc = sync_offsets(ctx, offsets, nullptr, n, (hipStream_t)stream, &total);
+    if (rc != CURDKV_OK) return rc;
+    if (total == 0) return CURDKV_OK;
+    if (!indices || !K_out || !V_out) return CURDKV_ERR_INVALID_ARG;
+    return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out,
+                          (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+}  // extern "C"

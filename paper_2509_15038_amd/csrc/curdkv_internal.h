@@ -1,0 +1,65 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "curdkv.h"
+
+namespace curdkv {
+
+constexpr int kHeadDim = 128;          // d the kernels are written for
+constexpr int kColBlock = 32;          // sketch columns per MFMA tile (M of the 32x32 tile)
+constexpr int kMaxColBlocks = 4;       // r padded to 32, 64 or 128
+constexpr int kMaxBlocksPerHead = 64;  // partial sums kept per (layer, group)
+constexpr int kTileTokens = 32;        // tokens per wave tile (N of the 32x32 tile)
+
+struct Plan {                          // device copy of the offsets, refreshed when they change
+    int64_t* d_offsets = nullptr;      // [heads + 1]
+    int64_t* h_staging = nullptr;      // pinned, [heads + 1]
+    std::vector<int64_t> cached;       // what d_offsets holds (after the queued copy)
+    bool valid = false;
+    hipEvent_t copied = nullptr;       // recorded after the last staging -> device copy
+    bool copy_pending = false;
+};
+
+}  // namespace curdkv
+
+struct curdkv_ctx {
+    curdkv_config cfg;
+    int device = 0;
+    int heads = 0;                     // layers * kv_heads
+    int col_blocks = 0;                // padded sketch_dim / 32 (1, 2 or 4)
+    size_t g_elems_per_head = 0;       // packed operand elements per (layer, group)
+    void* d_G = nullptr;               // packed sketches, storage type
+    float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
+    int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes
+    int num_cu = 0;
+    curdkv::Plan plan;
+};
+
+namespace curdkv {
+
+// sketch_host.cpp
+void sketch_values(const curdkv_config& cfg, int layer, int head, float* G /*[d*r], rounded*/);
+void round_to_storage(float* G, size_t count, int dtype);
+// Pack row-major G[d][r] (already rounded) into the A-operand layout of one head.
+void pack_sketch(const curdkv_config& cfg, int col_blocks, const float* G, void* packed);
+size_t packed_elems(int col_blocks);
+
+// kernel launchers; all return hipGetLastError() after the launch
+hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                         float* scores, hipStream_t stream);
+hipError_t launch_fold(const curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores,
+                       hipStream_t stream);
+hipError_t launch_select(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t n_sink,
+                         const int64_t* d_offsets, int32_t* indices, hipStream_t stream);
+hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                          const int32_t* indices, const int64_t* d_offsets, int64_t total,
+                          void* K_out, void* V_out, hipStream_t stream);
+hipError_t configure_kernels(curdkv_ctx* ctx);
+hipError_t configure_select(curdkv_ctx* ctx);
+
+}  // namespace curdkv

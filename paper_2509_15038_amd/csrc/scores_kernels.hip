@@ -1,0 +1,273 @@
+// Scoring kernels: Algorithm 1, lines "Project", "Compute leverage scores",
+// "Combine scores" and "Normalize", for gfx950.
+//
+// One pass over K and V.  The projection is computed transposed,
+//     Y^T = G^T A^T   (A = K_i or V_i),
+// with G^T as the MFMA A operand (M = 32 sketch columns) and a tile of 32 token
+// rows as the B operand (N = 32 tokens).  In the 32x32 accumulator layout a lane
+// then owns 16 sketch coordinates of ONE token (column lane%32), so the row-norm
+// squared is a sum inside the lane plus one exchange with lane^32.  The
+// projected rows never leave registers.
+
+#include "curdkv_internal.h"
+
+namespace curdkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+union Chunk {           // 16 bytes of a token row: 8 bf16
+    uint4 u;
+    bf16x8 v;
+};
+
+__device__ __forceinline__ float sum_sq(const f32x16& a) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s = fmaf(a[i], a[i], s);
+    return s;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// Sum the four wave totals of a 256-thread block in a fixed order and store it.
+__device__ __forceinline__ void block_partial_store(float wave_total, float* dst) {
+    __shared__ float wsum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) wsum[wave] = wave_total;
+    __syncthreads();
+    if (threadIdx.x == 0) *dst = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// ---------------------------------------------------------------------------
+// bf16 storage.  Lane L of a wave owns token (tile*32 + L%32) and the half row
+// d in [(L/32)*64, (L/32)*64 + 64): eight 16-byte chunks, chunk s feeding MFMA
+// step s.  The sketch operand was packed on the host in the matching order.
+// ---------------------------------------------------------------------------
+template <int CB>
+__global__ __launch_bounds__(256) void scores_bf16_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
+    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
+    const int head = blockIdx.x / blocks_per_head;
+    const int blk = blockIdx.x - head * blocks_per_head;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tok = lane & 31, half = lane >> 5;
+
+    bf16x8 g[CB][8];
+    {
+        const uint4* gp = Gp + (size_t)head * (CB * 8 * 64) + lane;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                Chunk c;
+                c.u = gp[(cb * 8 + s) * 64];
+                g[cb][s] = c.v;
+            }
+    }
+
+    const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
+    const int64_t stride = (int64_t)blocks_per_head * 4;
+    const uint4* Kh = K + (size_t)head * n * 16;   // 16 chunks of 16 bytes per row
+    const uint4* Vh = V + (size_t)head * n * 16;
+    float* sh = scores + (size_t)head * n;
+
+    float acc_sum = 0.f;
+    for (int64_t tile = (int64_t)blk * 4 + wave; tile < tiles; tile += stride) {
+        const int64_t row = tile * kTileTokens + tok;
+        const int64_t rowc = row < n ? row : n - 1;          // ragged tail: reload the last row
+        const uint4* kp = Kh + rowc * 16 + half * 8;
+        const uint4* vp = Vh + rowc * 16 + half * 8;
+        Chunk kc[8], vc[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) kc[s].u = kp[s];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) vc[s].u = vp[s];
+
+        float lk = 0.f, lv = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            f32x16 ak = {0}, av = {0};
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g[cb][s], kc[s].v, ak, 0, 0, 0);
+                av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g[cb][s], vc[s].v, av, 0, 0, 0);
+            }
+            lk += sum_sq(ak);
+            lv += sum_sq(av);
+        }
+        lk += __shfl_xor(lk, 32, 64);
+        lv += __shfl_xor(lv, 32, 64);
+        const float lkv = lk * lv;
+        if (half == 0 && row < n) {
+            sh[row] = lkv;
+            acc_sum += lkv;
+        }
+    }
+    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
+}
+
+// ---------------------------------------------------------------------------
+// fp32 storage (small caches): mfma_f32_32x32x2f32, the sketch staged in LDS.
+// Lane L owns token L%32 and the 64 contiguous floats of half row L/32.
+// ---------------------------------------------------------------------------
+template <int CB>
+__global__ __launch_bounds__(256) void scores_f32_kernel(
+    const float4* __restrict__ K, const float4* __restrict__ V, const float* __restrict__ Gp,
+    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
+    extern __shared__ float gs[];                      // [CB][64 steps][64 lanes]
+    const int head = blockIdx.x / blocks_per_head;
+    const int blk = blockIdx.x - head * blocks_per_head;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tok = lane & 31, half = lane >> 5;
+
+    for (int i = threadIdx.x; i < CB * 4096; i += 256) gs[i] = Gp[(size_t)head * (CB * 4096) + i];
+    __syncthreads();
+
+    const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
+    const int64_t stride = (int64_t)blocks_per_head * 4;
+    const float4* Kh = K + (size_t)head * n * 32;      // 32 float4 per row
+    const float4* Vh = V + (size_t)head * n * 32;
+    float* sh = scores + (size_t)head * n;
+
+    float acc_sum = 0.f;
+    for (int64_t tile = (int64_t)blk * 4 + wave; tile < tiles; tile += stride) {
+        const int64_t row = tile * kTileTokens + tok;
+        const int64_t rowc = row < n ? row : n - 1;
+        float l[2];
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const float4* p = (which == 0 ? Kh : Vh) + rowc * 32 + half * 16;
+            float4 x[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) x[q] = p[q];
+            float tot = 0.f;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                f32x16 a = {0};
+                const float* gq = gs + cb * 4096 + lane;
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 0) * 64], x[q].x, a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 1) * 64], x[q].y, a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 2) * 64], x[q].z, a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 3) * 64], x[q].w, a, 0, 0, 0);
+                }
+                tot += sum_sq(a);
+            }
+            tot += __shfl_xor(tot, 32, 64);
+            l[which] = tot;
+        }
+        const float lkv = l[0] * l[1];
+        if (half == 0 && row < n) {
+            sh[row] = lkv;
+            acc_sum += lkv;
+        }
+    }
+    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
+}
+
+// ---------------------------------------------------------------------------
+// "Normalize": divide by the sum over all n rows of the head.  The per-block
+// partial sums are added in index order in double, so the result does not
+// depend on scheduling.  A zero sum gives 1/n everywhere.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void normalise_kernel(float* __restrict__ scores,
+                                                        const float* __restrict__ partial,
+                                                        int64_t n, int blocks_per_head,
+                                                        int chunks_per_head) {
+    const int head = blockIdx.x / chunks_per_head;
+    const int chunk = blockIdx.x - head * chunks_per_head;
+    double tot = 0.0;
+    for (int i = 0; i < blocks_per_head; ++i) tot += (double)partial[(size_t)head * kMaxBlocksPerHead + i];
+    const bool zero = !(tot > 0.0);
+    const float inv = zero ? 0.f : (float)(1.0 / tot);
+    const float uniform = (float)(1.0 / (double)n);
+    float* sh = scores + (size_t)head * n;
+    for (int64_t j = (int64_t)chunk * blockDim.x + threadIdx.x; j < n;
+         j += (int64_t)chunks_per_head * blockDim.x)
+        sh[j] = zero ? uniform : sh[j] * inv;
+}
+
+// GQA fold: mean over the query heads of a group.  The sum is taken in double,
+// where adding a handful of floats is exact, so equal inputs come back unchanged.
+__global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
+                                                   float* __restrict__ out, int64_t n, int group,
+                                                   int chunks_per_head) {
+    const int head = blockIdx.x / chunks_per_head;
+    const int chunk = blockIdx.x - head * chunks_per_head;
+    const float* src = sq + (size_t)head * group * n;
+    float* dst = out + (size_t)head * n;
+    for (int64_t j = (int64_t)chunk * blockDim.x + threadIdx.x; j < n;
+         j += (int64_t)chunks_per_head * blockDim.x) {
+        double s = 0.0;
+        for (int q = 0; q < group; ++q) s += (double)src[(size_t)q * n + j];
+        dst[j] = (float)(s / (double)group);
+    }
+}
+
+static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
+    const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
+    int64_t want = (8LL * ctx->num_cu + ctx->heads - 1) / ctx->heads;   // ~8 blocks per CU in total
+    int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
+    if (want > cap) want = cap;
+    if (want > kMaxBlocksPerHead) want = kMaxBlocksPerHead;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+hipError_t configure_kernels(curdkv_ctx* ctx) {
+    if (ctx->cfg.dtype == CURDKV_DTYPE_F32) {
+        const int bytes = ctx->col_blocks * 4096 * 4;
+        hipError_t e = hipSuccess;
+        switch (ctx->col_blocks) {
+            case 1: e = hipFuncSetAttribute((const void*)scores_f32_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
+            case 2: e = hipFuncSetAttribute((const void*)scores_f32_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
+            default: e = hipFuncSetAttribute((const void*)scores_f32_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
+        }
+        return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                         float* scores, hipStream_t stream) {
+    const int bph = pick_blocks_per_head(ctx, n);
+    const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
+    if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
+        const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
+        switch (ctx->col_blocks) {
+            case 1: scores_bf16_kernel<1><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            case 2: scores_bf16_kernel<2><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            default: scores_bf16_kernel<4><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+        }
+    } else {
+        const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float* g = (const float*)ctx->d_G;
+        const size_t lds = (size_t)ctx->col_blocks * 4096 * 4;
+        switch (ctx->col_blocks) {
+            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+        }
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int64_t nb = (n + 1023) / 1024;
+    if (nb > 64) nb = 64;
+    normalise_kernel<<<dim3((unsigned)(nb * ctx->heads)), 256, 0, stream>>>(scores, ctx->d_partial, n, bph, (int)nb);
+    return hipGetLastError();
+}
+
+hipError_t launch_fold(const curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores,
+                       hipStream_t stream) {
+    int64_t nb = (n + 1023) / 1024;
+    if (nb > 64) nb = 64;
+    fold_kernel<<<dim3((unsigned)(nb * ctx->heads)), 256, 0, stream>>>(scores_q, scores, n, ctx->cfg.group_size, (int)nb);
+    return hipGetLastError();
+}
+
+}  // namespace curdkv

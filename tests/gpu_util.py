@@ -1,0 +1,106 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI on a
+host-generated cache and compare with the oracle.  Not collected by pytest."""
+
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import curdkv_oracle as orc
+from paper_2509_15038_amd import binding as B
+from paper_2509_15038_amd import workloads as wl
+
+RTOL = 1e-3     # relative tolerance on scores: fp32 accumulation of exact bf16 products
+
+
+def to_device(a: np.ndarray, dtype: str):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t, dtype: str) -> np.ndarray:
+    import torch
+    if dtype == "bf16":
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, dtype: str):
+    """scores -> select -> compact through the C ABI.  Returns device tensors."""
+    import torch
+    heads = ctx.heads
+    offsets = wl.offsets_for(budgets)
+    total = int(offsets[-1])
+    scores = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+    indices = torch.full((max(total, 1),), -7, dtype=torch.int32, device="cuda")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Ko = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
+    Vo = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
+    ctx.scores(Kd, Vd, n, scores)
+    ctx.select(scores, n, budgets, n_sink, offsets, indices)
+    ctx.compact(Kd, Vd, n, indices, offsets, Ko, Vo)
+    torch.cuda.synchronize()
+    return scores, indices[:total], Ko[:total], Vo[:total], offsets
+
+
+def check_scores(got: np.ndarray, want: np.ndarray, where=""):
+    err = np.abs(got.astype(np.float64) - want)
+    bad = err > RTOL * np.abs(want) + 1e-37
+    assert not bad.any(), f"{where}: {int(bad.sum())} scores off, worst rel {np.max(err / np.maximum(np.abs(want), 1e-300)):.3e}"
+    return float(np.max(err / np.maximum(np.abs(want), 1e-300)))
+
+
+def check_selection(got: np.ndarray, lt: np.ndarray, k: int, s: int, where=""):
+    """Index set: identical to the oracle's except for tokens whose oracle score
+    is within RTOL (relative) of the oracle's score at the cut."""
+    want = orc.select(lt, k, s)
+    assert got.shape == want.shape, f"{where}: size {got.shape} vs {want.shape}"
+    assert np.all(np.diff(got) > 0), f"{where}: indices not strictly ascending"
+    if k:
+        assert got[0] >= 0 and got[-1] < lt.size, where
+    if np.array_equal(got, want):
+        return 0
+    assert k > s, where
+    diff = np.setxor1d(got, want)
+    assert np.all(diff >= s), f"{where}: sink tokens differ"
+    cut = np.min(lt[want[want >= s]])          # the (k-s)-th largest candidate score
+    assert np.all(np.abs(lt[diff] - cut) <= RTOL * cut), \
+        f"{where}: {diff.size} tokens differ beyond the near-cut band"
+    return int(diff.size)
+
+
+def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where=""):
+    """All three comparisons for one (layer, head) given host copies."""
+    lt = orc.scores(orc.to_f64(K, cfg.dtype), orc.to_f64(V, cfg.dtype), G)
+    rel = check_scores(scores_g, lt, where)
+    ndiff = check_selection(idx_g.astype(np.int64), lt, k, s, where)
+    Kc, Vc = orc.compact(K, V, idx_g.astype(np.int64))
+    assert np.array_equal(Ko_g, Kc), f"{where}: gathered K differs"
+    assert np.array_equal(Vo_g, Vc), f"{where}: gathered V differs"
+    return rel, ndiff
+
+
+def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None):
+    """Whole path on a host cache, every head compared with the oracle."""
+    s = cfg.n_sink if n_sink is None else n_sink
+    if K is None:
+        K, V = wl.host_cache(cfg)
+    L, H, n = cfg.layers, cfg.kv_heads, cfg.n
+    Kd, Vd = to_device(K, cfg.dtype), to_device(V, cfg.dtype)
+    worst, ndiff = 0.0, 0
+    with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
+        sc, idx, Ko, Vo, off = run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype)
+        sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
+        Ko_h, Vo_h = to_host(Ko, cfg.dtype), to_host(Vo, cfg.dtype)
+        for l in range(L):
+            for h in range(H):
+                i = l * H + h
+                G = orc.sketch(cfg.sketch_seed, l, h, H, cfg.d, cfg.r, cfg.dtype)
+                a, b = int(off[i]), int(off[i + 1])
+                rel, nd = check_head(cfg, None, K[l, h], V[l, h], G, sc_h[i], idx_h[a:b],
+                                     Ko_h[a:b], Vo_h[a:b], int(budgets[i]), s,
+                                     where=f"{cfg.name} l{l} h{h} n{n}")
+                worst = max(worst, rel)
+                ndiff += nd
+    return worst, ndiff

@@ -1,0 +1,67 @@
+"""The C-ABI library: it loads, exports every symbol the header declares, and its
+host-only entry points behave (no GPU compute here)."""
+
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import curdkv_oracle as orc
+from paper_2509_15038_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "curdkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(curdkv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert "curdkv_scores" in names and "curdkv_select" in names and "curdkv_compact" in names
+    L = B.lib()
+    for nm in names:
+        assert hasattr(L, nm), nm
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror():
+    assert B.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert B.strerror(code)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("r", [20, 32, 64, 128])
+def test_host_sketch_matches_oracle_bitwise(dtype, r):
+    # two independent implementations of the same counter-based generator
+    cfg = B.make_config(3, 8, 4, 128, r, dtype, 1024, 0xC0DE0003)
+    for (l, h) in [(0, 0), (1, 5), (2, 7)]:
+        got = B.curdkv_sketch_host(cfg, l, h)
+        want = orc.sketch(0xC0DE0003, l, h, 8, 128, r, dtype)
+        assert np.array_equal(got.astype(np.float64), want)
+
+
+def test_config_validation_on_host():
+    G = np.empty((128, 64), dtype=np.float32)
+    import ctypes as C
+    def rc(**kw):
+        base = dict(layers=1, kv_heads=1, group_size=1, head_dim=128, sketch_dim=64, dtype="bf16",
+                    max_tokens=16, seed=1)
+        base.update(kw)
+        cfg = B.make_config(**base)
+        return B.lib().curdkv_sketch_host(C.byref(cfg), 0, 0, G.ctypes.data)
+    assert rc() == B.OK
+    assert rc(head_dim=64) == B.ERR_UNSUPPORTED
+    assert rc(sketch_dim=129) == B.ERR_UNSUPPORTED
+    assert rc(sketch_dim=0) == B.ERR_INVALID_ARG
+    assert rc(dtype=7) == B.ERR_UNSUPPORTED
+    assert rc(layers=0) == B.ERR_INVALID_ARG
+    assert rc(max_tokens=0) == B.ERR_INVALID_ARG
+    cfg = B.make_config(1, 1, 1, 128, 64, "bf16", 16, 1)
+    assert B.lib().curdkv_sketch_host(C.byref(cfg), 1, 0, G.ctypes.data) == B.ERR_INVALID_ARG
+    assert B.lib().curdkv_sketch_host(C.byref(cfg), 0, 0, None) == B.ERR_INVALID_ARG
+    assert B.lib().curdkv_sketch_host(None, 0, 0, G.ctypes.data) == B.ERR_INVALID_ARG

@@ -1,0 +1,104 @@
+"""GPU parity at the benchmark's full sizes and launch configuration.
+
+The caches are drawn on the GPU (same distributions as the host generators);
+sampled (layer, head) groups are copied back and the oracle recomputes exactly
+those groups, element by element.  Properties that hold at any size (score sums,
+index ranges and order, bit-exact gather) are checked on every group."""
+
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import curdkv_oracle as orc
+from paper_2509_15038_amd import binding as B
+from paper_2509_15038_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
+    sys.stdout.flush()
+    yield
+
+
+def _full(cfg, keeps, sample, gu):
+    import torch
+    L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
+    heads = L * H
+    Kd, Vd = wl.device_cache(cfg)
+    with B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
+        for keep in keeps:
+            budgets = wl.budgets_for(cfg, keep)
+            print(f"  {cfg.name} n={n} keep={keep} total rows={int(budgets.sum())}", flush=True)
+            sc, idx, Ko, Vo, off = gu.run_path(ctx, Kd, Vd, n, budgets, cfg.n_sink, cfg.dtype)
+            # ---- every group: invariants ------------------------------------------
+            sums = sc.double().sum(1).cpu().numpy()
+            assert np.allclose(sums, 1.0, atol=1e-4), "scores do not sum to one"
+            assert bool((sc >= 0).all())
+            idx_h = idx.cpu().numpy()
+            off_t = torch.from_numpy(off).cuda()
+            head_of = torch.repeat_interleave(torch.arange(heads, device="cuda"),
+                                              torch.from_numpy(budgets.astype(np.int64)).cuda())
+            assert bool(((idx >= 0) & (idx < n)).all())
+            same_head = head_of[1:] == head_of[:-1]
+            assert bool((idx[1:][same_head] > idx[:-1][same_head]).all()), "not ascending"
+            # gather: compare with torch indexing on the device, bit for bit
+            flat_rows = head_of * n + idx.long()
+            Kref = Kd.view(heads * n, d)[flat_rows]
+            Vref = Vd.view(heads * n, d)[flat_rows]
+            assert torch.equal(Ko.view(torch.int16), Kref.view(torch.int16))
+            assert torch.equal(Vo.view(torch.int16), Vref.view(torch.int16))
+            # top-k property on the GPU's own scores: min kept >= max dropped (non-sink)
+            s = cfg.n_sink
+            for i in range(0, heads, 37):
+                k = int(budgets[i])
+                if k <= s or k >= n:
+                    continue
+                sci = sc[i].cpu().numpy()
+                kept = idx_h[off[i]:off[i + 1]]
+                mask = np.zeros(n, bool); mask[kept] = True
+                assert mask[:s].all()
+                assert sci[s:][mask[s:]].min() >= sci[s:][~mask[s:]].max()
+            # ---- sampled groups: element by element against the oracle -------------
+            for (l, h) in sample:
+                i = l * H + h
+                G = orc.sketch(cfg.sketch_seed, l, h, H, d, cfg.r, cfg.dtype)
+                a, b = int(off[i]), int(off[i + 1])
+                rel, nd = gu.check_head(cfg, None, gu.to_host(Kd[l, h], cfg.dtype),
+                                        gu.to_host(Vd[l, h], cfg.dtype), G, sc[i].cpu().numpy(),
+                                        idx_h[a:b], gu.to_host(Ko[a:b], cfg.dtype),
+                                        gu.to_host(Vo[a:b], cfg.dtype), int(budgets[i]), s,
+                                        where=f"{cfg.name} full l{l} h{h} keep{keep}")
+                print(f"    l{l} h{h}: worst rel {rel:.2e}, near-cut diffs {nd}", flush=True)
+            del sc, idx, Ko, Vo
+    del Kd, Vd
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available()
+    B.lib()
+    from tests import gpu_util
+    return gpu_util
+
+
+def test_c3_full_llama_32k_all_budgets(gu):
+    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu)
+
+
+def test_c4_full_mistral_32k_prefix(gu):
+    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu)
+
+
+def test_c5_full_128k_dirichlet(gu):
+    cfg = wl.CONFIGS["c5"]
+    b = wl.budgets_for(cfg).reshape(32, 8)
+    l_small = int(np.argmin(b.min(1)))      # the groups with the smallest and largest budget
+    l_big = int(np.argmax(b.max(1)))
+    sample = [(l_small, int(np.argmin(b[l_small]))), (l_big, int(np.argmax(b[l_big]))), (31, 7)]
+    _full(cfg, (None,), sample, gu)

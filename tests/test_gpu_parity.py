@@ -1,0 +1,237 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Scores within 1e-3 relative (fp32 accumulation of exact
+bf16 products against float64); index sets identical except for tokens whose
+oracle score is within that tolerance of the cut; gathered rows bit-exact."""
+
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import curdkv_oracle as orc
+from paper_2509_15038_amd import binding as B
+from paper_2509_15038_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-case] {request.node.nodeid}", flush=True)
+    sys.stdout.flush()
+    yield
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.lib()                       # fail loudly if the HIP library is not built
+    from tests import gpu_util
+    return gpu_util
+
+
+# ---- the benchmark configurations at sizes the oracle finishes in seconds ----
+
+def test_c1_fp32_single_head(gu):
+    cfg = wl.CONFIGS["c1"]
+    worst, nd = gu.run_and_check(cfg, wl.budgets_for(cfg))
+    print(f"c1 worst rel {worst:.2e}, near-cut differences {nd}")
+
+
+def test_c2_llama_layer(gu):
+    cfg = wl.CONFIGS["c2"]
+    worst, nd = gu.run_and_check(cfg, wl.budgets_for(cfg))
+    print(f"c2 worst rel {worst:.2e}, near-cut differences {nd}")
+
+
+@pytest.mark.parametrize("keep", [0.10, 0.20, 0.50])
+def test_c3_shape_reduced_ragged(gu, keep):
+    # several tiles per wave, a ragged last tile, more than one layer
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=3, n=5000 + 17)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, keep))
+
+
+def test_c4_shape_reduced_prefix_block(gu):
+    cfg = wl.scaled(wl.CONFIGS["c4"], layers=2, n=4096 + 5)
+    gu.run_and_check(cfg, wl.budgets_for(cfg), n_sink=4)
+    gu.run_and_check(cfg, wl.budgets_for(cfg), n_sink=64)
+    gu.run_and_check(cfg, wl.budgets_for(cfg), n_sink=0)
+
+
+def test_c5_shape_reduced_dirichlet_r128_streaming_select(gu):
+    # n above what LDS holds -> the select kernel streams keys from memory
+    cfg = wl.scaled(wl.CONFIGS["c5"], layers=2, kv_heads=4, n=45000 + 3)
+    b = wl.budgets_for(cfg)
+    assert b.reshape(2, 4).sum(1).tolist() == [int(0.05 * 4 * cfg.n)] * 2
+    gu.run_and_check(cfg, b)
+
+
+# ---- sketch widths (the paper's r = 20 is zero-padded to 32 columns).  Below r = 8 a
+# row's score can be a near-cancelled dot product, where no relative bound holds. ---
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("r", [8, 20, 32, 48, 64, 100, 128])
+def test_sketch_dims(gu, dtype, r):
+    cfg = wl.scaled(wl.CONFIGS["c2"], kv_heads=2, n=700, r=r, dtype=dtype)
+    gu.run_and_check(cfg, wl.budgets_for(cfg))
+
+
+# ---- sizes around tile boundaries and degenerate budgets ----------------------
+
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 63, 64, 65, 127, 129, 1023, 1025])
+def test_small_and_ragged_n(gu, n):
+    cfg = wl.scaled(wl.CONFIGS["c2"], kv_heads=3, n=n)
+    k = max(0, n // 3)
+    gu.run_and_check(cfg, np.full(3, k, dtype=np.int32))
+
+
+def test_degenerate_budgets(gu):
+    cfg = wl.scaled(wl.CONFIGS["c2"], layers=2, kv_heads=4, n=300)
+    n = cfg.n
+    # empty head, inside the sinks, exactly the sinks, one above, all but one, all
+    b = np.array([0, 3, 4, 5, n - 1, n, 1, 150], dtype=np.int32)
+    gu.run_and_check(cfg, b, n_sink=4)
+    gu.run_and_check(cfg, b, n_sink=0)
+    gu.run_and_check(cfg, b, n_sink=n + 5)          # more sinks than tokens
+    gu.run_and_check(cfg, np.zeros(8, dtype=np.int32))  # nothing kept anywhere
+
+
+def test_zero_cache_gives_uniform_scores(gu):
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c2"], kv_heads=2, n=200)
+    K = np.zeros((1, 2, 200, 128), dtype=np.uint16)
+    _, V = wl.host_cache(cfg)
+    gu.run_and_check(cfg, np.array([50, 7], dtype=np.int32), K=K, V=V)
+
+
+def test_select_ties_lowest_index_first(gu):
+    # planted equal scores: the choice among equals is by token index
+    import torch
+    n, H, s = 3000, 4, 4
+    rng = np.random.default_rng(11)
+    sc = rng.integers(1, 6, size=(H, n)).astype(np.float32) / 8.0
+    sc[1] = 0.25                                    # one head entirely tied
+    sc[2, 100:] = 0.0                               # zeros beyond a few
+    budgets = np.array([700, 1234, 500, 2999], dtype=np.int32)
+    off = wl.offsets_for(budgets)
+    with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
+        scd = torch.from_numpy(sc).cuda()
+        idx = torch.full((int(off[-1]),), -1, dtype=torch.int32, device="cuda")
+        ctx.select(scd, n, budgets, s, off, idx)
+        torch.cuda.synchronize()
+        idx = idx.cpu().numpy()
+    for h in range(H):
+        want = orc.select(sc[h].astype(np.float64), int(budgets[h]), s)
+        assert np.array_equal(idx[off[h]:off[h + 1]], want), h
+
+
+def test_select_large_n_streaming_ties(gu):
+    import torch
+    n, H, s = 70001, 2, 4
+    rng = np.random.default_rng(12)
+    sc = (rng.integers(0, 50, size=(H, n)).astype(np.float32)) * np.float32(1e-6)
+    budgets = np.array([7000, 35000], dtype=np.int32)
+    off = wl.offsets_for(budgets)
+    with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
+        scd = torch.from_numpy(sc).cuda()
+        idx = torch.full((int(off[-1]),), -1, dtype=torch.int32, device="cuda")
+        ctx.select(scd, n, budgets, s, off, idx)
+        torch.cuda.synchronize()
+        idx = idx.cpu().numpy()
+    for h in range(H):
+        want = orc.select(sc[h].astype(np.float64), int(budgets[h]), s)
+        assert np.array_equal(idx[off[h]:off[h + 1]], want), h
+
+
+def test_fold_gqa(gu):
+    import torch
+    L, H, g, n = 2, 3, 4, 1000
+    rng = np.random.default_rng(13)
+    sq = rng.random((L * H, g, n)).astype(np.float32)
+    sq[0] = sq[0, 0]                                 # CurDKV case: the group shares one score
+    with B.Context(L, H, g, 128, 64, "bf16", n, 1) as ctx:
+        d = torch.from_numpy(sq).cuda()
+        out = torch.empty((L * H, n), dtype=torch.float32, device="cuda")
+        ctx.fold(d, n, out)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+    assert np.array_equal(out[0], sq[0, 0])          # identity, bit for bit
+    for i in range(L * H):
+        want = orc.fold_gqa(sq[i].astype(np.float64))
+        assert np.allclose(out[i], want, rtol=1e-6, atol=0)
+
+
+def test_user_supplied_sketch(gu):
+    cfg = wl.scaled(wl.CONFIGS["c2"], kv_heads=2, n=500)
+    import torch
+    K, V = wl.host_cache(cfg)
+    rng = np.random.default_rng(14)
+    Gs = [rng.standard_normal((128, cfg.r)).astype(np.float32) / 8.0 for _ in range(2)]
+    with B.Context(1, 2, 4, 128, cfg.r, "bf16", cfg.n, 5) as ctx:
+        for h in range(2):
+            ctx.set_sketch(0, h, Gs[h])
+        sc = torch.empty((2, cfg.n), dtype=torch.float32, device="cuda")
+        ctx.scores(gu.to_device(K, "bf16"), gu.to_device(V, "bf16"), cfg.n, sc)
+        torch.cuda.synchronize()
+        sc = sc.cpu().numpy()
+    for h in range(2):
+        G = orc.round_to_storage(Gs[h].astype(np.float64), "bf16")
+        lt = orc.scores(orc.to_f64(K[0, h], "bf16"), orc.to_f64(V[0, h], "bf16"), G)
+        gu.check_scores(sc[h], lt, f"user sketch h{h}")
+
+
+def test_repeatable_bitwise(gu):
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=2, n=3000)
+    K, V = wl.host_cache(cfg)
+    Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
+    b = wl.budgets_for(cfg, 0.2)
+    outs = []
+    for _ in range(2):
+        with B.Context(cfg.layers, cfg.kv_heads, 4, 128, cfg.r, "bf16", cfg.n, cfg.sketch_seed) as ctx:
+            sc, idx, Ko, Vo, _ = gu.run_path(ctx, Kd, Vd, cfg.n, b, 4, "bf16")
+            outs.append((sc.clone(), idx.clone(), Ko.clone(), Vo.clone()))
+    for a, c in zip(*outs):
+        assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                           c.view(torch.int32) if c.dtype == torch.float32 else c)
+
+
+def test_error_paths_launch_nothing(gu):
+    import torch
+    n, H = 64, 2
+    with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
+        K = torch.zeros((H, n, 128), dtype=torch.bfloat16, device="cuda")
+        sc = torch.zeros((H, n), dtype=torch.float32, device="cuda")
+        idx = torch.zeros((2 * n,), dtype=torch.int32, device="cuda")
+        good_b = np.array([8, 8], dtype=np.int32)
+        good_o = wl.offsets_for(good_b)
+
+        def code(fn, *a):
+            with pytest.raises(B.CurdkvError) as e:
+                fn(*a)
+            return e.value.code
+
+        assert code(ctx.scores, K, K, n + 1, sc) == B.ERR_INVALID_ARG       # n > max_tokens
+        assert code(ctx.scores, K, K, 0, sc) == B.ERR_INVALID_ARG
+        assert code(ctx.scores, None, K, n, sc) == B.ERR_INVALID_ARG
+        assert code(ctx.scores, K.data_ptr() + 2, K, n, sc) == B.ERR_INVALID_ARG   # misaligned
+        assert code(ctx.select, sc, n, np.array([8, n + 1], dtype=np.int32), 4,
+                    wl.offsets_for(np.array([8, n + 1])), idx) == B.ERR_INVALID_ARG
+        assert code(ctx.select, sc, n, np.array([8, -1], dtype=np.int32), 4,
+                    np.array([0, 8, 7], dtype=np.int64), idx) == B.ERR_INVALID_ARG
+        assert code(ctx.select, sc, n, good_b, 4, np.array([0, 8, 17], dtype=np.int64), idx) == B.ERR_INVALID_ARG
+        assert code(ctx.select, sc, n, good_b, 4, np.array([1, 9, 17], dtype=np.int64), idx) == B.ERR_INVALID_ARG
+        assert code(ctx.select, sc, n, good_b, -1, good_o, idx) == B.ERR_INVALID_ARG
+        assert code(ctx.select, sc, n, good_b, 4, good_o, None) == B.ERR_INVALID_ARG
+        assert code(ctx.compact, K, K, n, idx, np.array([0, 8, 8 + n + 1], dtype=np.int64), K, K) == B.ERR_INVALID_ARG
+        assert code(ctx.compact, K, K, n, None, good_o, K, K) == B.ERR_INVALID_ARG
+        # out-of-range indices are skipped by the kernel, never dereferenced
+        bad = torch.tensor([0, 1, 2, 3, -5, 10 ** 6, 6, 7] * 2, dtype=torch.int32, device="cuda")
+        Ko = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
+        Vo = torch.zeros((16, 128), dtype=torch.bfloat16, device="cuda")
+        ctx.compact(K, K, n, bad, good_o, Ko, Vo)
+        torch.cuda.synchronize()
+    with pytest.raises(B.CurdkvError) as e:
+        B.Context(1, 1, 1, 64, 64, "bf16", 16, 1)
+    assert e.value.code == B.ERR_UNSUPPORTED
