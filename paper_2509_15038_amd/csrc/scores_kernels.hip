@@ -3,11 +3,13 @@
 //
 // One pass over K and V.  The projection is computed transposed,
 //     Y^T = G^T A^T   (A = K_i or V_i),
-// with G^T as the MFMA A operand (M = 32 sketch columns) and a tile of 32 token
-// rows as the B operand (N = 32 tokens).  In the 32x32 accumulator layout a lane
-// then owns 16 sketch coordinates of ONE token (column lane%32), so the row-norm
-// squared is a sum inside the lane plus one exchange with lane^32.  The
-// projected rows never leave registers.
+// with G^T as the MFMA A operand (M = sketch columns) and a tile of token rows
+// as the B operand (N = tokens).  In the accumulator layout a lane then owns
+// several sketch coordinates of ONE token (its column), so the row-norm squared
+// is a sum inside the lane plus one or two lane exchanges.  The projected rows
+// never leave registers.
+
+#include <type_traits>
 
 #include "curdkv_internal.h"
 
@@ -44,68 +46,168 @@ __device__ __forceinline__ void block_partial_store(float wave_total, float* dst
 }
 
 // ---------------------------------------------------------------------------
-// bf16 storage.  Lane L of a wave owns token (tile*32 + L%32) and the half row
-// d in [(L/32)*64, (L/32)*64 + 64): eight 16-byte chunks, chunk s feeding MFMA
-// step s.  The sketch operand was packed on the host in the matching order.
+// bf16 storage: mfma_f32_16x16x32_bf16.  A wave owns a contiguous range of
+// 32-token tiles and works through it in pairs (64 tokens); a tile is two
+// sub-tiles of 16 tokens.  In a sub-tile lane L owns token L%16 and, at MFMA
+// step s (0..3), the 16 bytes holding d in [s*32 + (L/16)*8, +8): the four lanes
+// of a token read 64 contiguous bytes per load instruction and the wave reads
+// whole 256-byte rows over the four steps, which the memory system serves as
+// well as a fully coalesced stream.  The accumulator of lane L holds sketch
+// coordinates cb*16 + 4*(L/16) + {0..3} of token L%16, so the row-norm squared
+// is a sum in the lane plus exchanges between the four 16-lane rows, done with
+// the gfx950 lane-swap instructions (no LDS round trip).  After the exchange
+// every lane of a token holds its score; lane row j keeps the score of sub-tile
+// j of the pair, so a pair ends in ONE coalesced 256-byte store of 64 scores.
+// Loads of a tile are issued as soon as the MFMAs that used its buffer are
+// done (two register buffers).  CB = padded sketch width / 16.
 // ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+struct TileRegs {
+    Chunk k[2][4];
+    Chunk v[2][4];
+};
+
+// a[32..63] <-> b[0..31]
+__device__ __forceinline__ void swap_halves(float& a, float& b) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+// odd 16-lane rows of a <-> even 16-lane rows of b
+__device__ __forceinline__ void swap_rows(float& a, float& b) {
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
+// lk, lv: per-lane partial sums of a token held by lanes t, t+16, t+32, t+48.
+// Returns (sum of the four lk) * (sum of the four lv) in all four lanes.
+__device__ __forceinline__ float combine_rows(float lk, float lv) {
+    swap_halves(lk, lv);                 // lk = [lk rows 0,1 | lv rows 0,1], lv = [lk rows 2,3 | lv rows 2,3]
+    float x = lk + lv;                   // rows: lk0+lk2, lk1+lk3, lv0+lv2, lv1+lv3
+    float y = x;
+    swap_rows(x, y);                     // x = rows 0,0,2,2 ; y = rows 1,1,3,3
+    float z = x + y;                     // rows: LK, LK, LV, LV
+    float w = z;
+    swap_halves(z, w);                   // z = LK everywhere, w = LV everywhere
+    return z * w;
+}
+
 template <int CB>
-__global__ __launch_bounds__(256) void scores_bf16_kernel(
+__global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tok = lane & 31, half = lane >> 5;
+    const int tok = lane & 15, q = lane >> 4;
 
-    bf16x8 g[CB][8];
+    bf16x8 g[CB][4];
     {
-        const uint4* gp = Gp + (size_t)head * (CB * 8 * 64) + lane;
+        const uint4* gp = Gp + (size_t)head * (CB * 4 * 64) + lane;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
+            for (int s = 0; s < 4; ++s) {
                 Chunk c;
-                c.u = gp[(cb * 8 + s) * 64];
+                c.u = gp[(cb * 4 + s) * 64];
                 g[cb][s] = c.v;
             }
     }
 
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
-    const int64_t stride = (int64_t)blocks_per_head * 4;
-    const uint4* Kh = K + (size_t)head * n * 16;   // 16 chunks of 16 bytes per row
+    const int64_t waves_per_head = (int64_t)blocks_per_head * 4;
+    int64_t per_wave = (tiles + waves_per_head - 1) / waves_per_head;
+    per_wave += per_wave & 1;                                   // whole pairs
+    const int64_t t_begin = ((int64_t)blk * 4 + wave) * per_wave;
+    const int64_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
+    const uint4* Kh = K + (size_t)head * n * 16;                // 16 chunks of 16 bytes per row
     const uint4* Vh = V + (size_t)head * n * 16;
     float* sh = scores + (size_t)head * n;
-
     float acc_sum = 0.f;
-    for (int64_t tile = (int64_t)blk * 4 + wave; tile < tiles; tile += stride) {
-        const int64_t row = tile * kTileTokens + tok;
-        const int64_t rowc = row < n ? row : n - 1;          // ragged tail: reload the last row
-        const uint4* kp = Kh + rowc * 16 + half * 8;
-        const uint4* vp = Vh + rowc * 16 + half * 8;
-        Chunk kc[8], vc[8];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) kc[s].u = kp[s];
-#pragma unroll
-        for (int s = 0; s < 8; ++s) vc[s].u = vp[s];
+    float pend = 0.f;                                           // this lane's score of the current pair
 
-        float lk = 0.f, lv = 0.f;
+    // CHECK = false is for tiles known to lie entirely below n: no clamping, no
+    // predicate, hence no branch, which keeps the steady-state loop one basic
+    // block so that the compiler's wait counts let loads stay in flight.
+    auto load_tile = [&](TileRegs& r, int64_t tile, auto check) {
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            f32x16 ak = {0}, av = {0};
+        for (int t2 = 0; t2 < 2; ++t2) {
+            int64_t row = tile * kTileTokens + t2 * 16 + tok;
+            if (decltype(check)::value) row = row < n ? row : n - 1;   // ragged tail: reload the last row
+            const uint4* kp = Kh + row * 16 + q;
+            const uint4* vp = Vh + row * 16 + q;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g[cb][s], kc[s].v, ak, 0, 0, 0);
-                av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g[cb][s], vc[s].v, av, 0, 0, 0);
-            }
-            lk += sum_sq(ak);
-            lv += sum_sq(av);
+            for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) r.v[t2][s].u = vp[s * 4];
         }
-        lk += __shfl_xor(lk, 32, 64);
-        lv += __shfl_xor(lv, 32, 64);
-        const float lkv = lk * lv;
-        if (half == 0 && row < n) {
-            sh[row] = lkv;
-            acc_sum += lkv;
+    };
+    auto compute_tile = [&](const TileRegs& r, int slot) {      // slot: 0 = first tile of the pair
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            f32x4 ak[CB], av[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) { ak[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; av[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    ak[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g[cb][s], r.k[t2][s].v, ak[cb], 0, 0, 0);
+                    av[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g[cb][s], r.v[t2][s].v, av[cb], 0, 0, 0);
+                }
+            float lk = 0.f, lv = 0.f;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    lk = fmaf(ak[cb][e], ak[cb][e], lk);
+                    lv = fmaf(av[cb][e], av[cb][e], lv);
+                }
+            const float lkv = combine_rows(lk, lv);
+            pend = (q == slot * 2 + t2) ? lkv : pend;
+        }
+    };
+    auto store_pair = [&](int64_t tile, auto check) {           // lane L holds token tile*32 + L
+        const int64_t row = tile * kTileTokens + lane;
+        if (!decltype(check)::value || row < n) {
+            sh[row] = pend;
+            acc_sum += pend;
+        }
+    };
+    const std::true_type checked;
+    const std::false_type unchecked;
+
+    if (t_begin < t_end) {
+        TileRegs ra, rb;
+        int64_t t = t_begin;
+        // both buffers are always filled (a lone tile is simply loaded twice): a
+        // conditional load here would make every wait in the loop below pessimistic
+        load_tile(ra, t, checked);
+        load_tile(rb, t + 1 < t_end ? t + 1 : t, checked);
+        const int64_t full = n / kTileTokens;                   // tiles with all 32 rows below n
+        const int64_t t_steady = t_end < full ? t_end : full;
+        for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 are whole
+            compute_tile(ra, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(ra, t + 2, unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_tile(rb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(rb, t + 3, unchecked);
+            store_pair(t, unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (; t < t_end; t += 2) {                             // last one or two pairs
+            compute_tile(ra, 0);
+            if (t + 2 < t_end) load_tile(ra, t + 2, checked);
+            if (t + 1 < t_end) {
+                compute_tile(rb, 1);
+                if (t + 3 < t_end) load_tile(rb, t + 3, checked);
+            }
+            store_pair(t, checked);                             // an absent second tile lies beyond n
         }
     }
     block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
@@ -240,10 +342,10 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
     const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
-        switch (ctx->col_blocks) {
-            case 1: scores_bf16_kernel<1><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            case 2: scores_bf16_kernel<2><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            default: scores_bf16_kernel<4><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+        switch (ctx->col_blocks) {   // 16-column MFMA blocks = 2 per 32 padded columns
+            case 1: scores_bf16_kernel<2><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            case 2: scores_bf16_kernel<4><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            default: scores_bf16_kernel<8><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
         }
     } else {
         const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float* g = (const float*)ctx->d_G;
