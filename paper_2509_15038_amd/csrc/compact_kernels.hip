@@ -5,65 +5,67 @@
 // by head, so ragged budgets balance by themselves.  A row is copied by a group
 // of lanes, 16 bytes per lane, which makes every load and store of a wave cover
 // whole rows: 256-byte rows are read at scattered (ascending) addresses and
-// written contiguously.
+// written contiguously.  Rows are used once, so loads and stores are marked
+// non-temporal.  The head that owns the first row of each block, and where that
+// head's rows end, come from a small table the host builds from the offsets, so
+// no block has to search and a row address depends on one index load only.
 
 #include "curdkv_internal.h"
 
 namespace curdkv {
 
-constexpr int kRowsPerBlock = 64;
-
-// first head h with offsets[h+1] > p  (offsets non-decreasing, offsets[heads] > p)
-__device__ __forceinline__ int head_of_row(const int64_t* __restrict__ offsets, int heads, int64_t p) {
-    int lo = 0, hi = heads - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (offsets[mid + 1] > p) hi = mid; else lo = mid + 1;
-    }
-    return lo;
-}
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // ROW_U4: 16-byte chunks per row (16 for bf16 d=128, 32 for fp32 d=128)
 template <int ROW_U4>
 __global__ __launch_bounds__(256) void compact_kernel(
-    const uint4* __restrict__ K, const uint4* __restrict__ V, int64_t n,
-    const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets, int heads,
-    int64_t total, uint4* __restrict__ K_out, uint4* __restrict__ V_out) {
+    const u32x4* __restrict__ K, const u32x4* __restrict__ V, int64_t n,
+    const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
+    const BlockInfo* __restrict__ block_info, int64_t total,
+    u32x4* __restrict__ K_out, u32x4* __restrict__ V_out) {
     constexpr int kRowsPerIter = 256 / ROW_U4;
-    constexpr int kIters = kRowsPerBlock / kRowsPerIter;
+    constexpr int kIters = 4;                                   // rows in flight per thread
+    constexpr int kPasses = kCompactRowsPerBlock / (kRowsPerIter * kIters);
     const int c = threadIdx.x % ROW_U4;
     const int rsub = threadIdx.x / ROW_U4;
-    const int64_t p0 = (int64_t)blockIdx.x * kRowsPerBlock;
-    const int h0 = head_of_row(offsets, heads, p0);            // block-uniform
+    const int64_t p0 = (int64_t)blockIdx.x * kCompactRowsPerBlock;
+    const BlockInfo bi = block_info[blockIdx.x];
+    int h = bi.head;                                            // head of row p0
+    int64_t head_end = bi.head_end;                             // offsets[h + 1]
 
-    const uint4* src_k[kIters];
-    const uint4* src_v[kIters];
-    bool ok[kIters];
+    for (int pass = 0; pass < kPasses; ++pass) {
+        // index loads first and without branches, so that they are all in flight together
+        int32_t idx[kIters];
 #pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-        const int64_t p = p0 + it * kRowsPerIter + rsub;
-        ok[it] = p < total;
-        int64_t idx = 0;
-        int h = h0;
-        if (ok[it]) {
-            while (offsets[h + 1] <= p) ++h;                    // skips empty heads too
-            idx = indices[p];
-            ok[it] = idx >= 0 && idx < n;                       // never read outside the cache
+        for (int it = 0; it < kIters; ++it) {
+            const int64_t p = p0 + (pass * kIters + it) * kRowsPerIter + rsub;
+            idx[it] = indices[p < total ? p : total - 1];
         }
-        const size_t row = ((size_t)h * n + (ok[it] ? idx : 0)) * ROW_U4 + c;
-        src_k[it] = K + row;
-        src_v[it] = V + row;
-    }
-    uint4 vk[kIters], vv[kIters];
+        const u32x4* src_k[kIters];
+        const u32x4* src_v[kIters];
+        bool ok[kIters];
 #pragma unroll
-    for (int it = 0; it < kIters; ++it)
-        if (ok[it]) { vk[it] = *src_k[it]; vv[it] = *src_v[it]; }
+        for (int it = 0; it < kIters; ++it) {
+            const int64_t p = p0 + (pass * kIters + it) * kRowsPerIter + rsub;
+            while (head_end <= p && p < total) head_end = offsets[++h + 1];   // rows ascend: h only moves forward
+            ok[it] = p < total && idx[it] >= 0 && idx[it] < n;  // never read outside the cache
+            const size_t row = ((size_t)h * n + (ok[it] ? idx[it] : 0)) * ROW_U4 + c;
+            src_k[it] = K + row;
+            src_v[it] = V + row;
+        }
+        u32x4 vk[kIters], vv[kIters];
 #pragma unroll
-    for (int it = 0; it < kIters; ++it) {
-        const int64_t p = p0 + it * kRowsPerIter + rsub;
-        if (ok[it]) {
-            K_out[(size_t)p * ROW_U4 + c] = vk[it];
-            V_out[(size_t)p * ROW_U4 + c] = vv[it];
+        for (int it = 0; it < kIters; ++it) {
+            vk[it] = __builtin_nontemporal_load(src_k[it]);     // row 0 of the head when !ok: in bounds, unused
+            vv[it] = __builtin_nontemporal_load(src_v[it]);
+        }
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int64_t p = p0 + (pass * kIters + it) * kRowsPerIter + rsub;
+            if (ok[it]) {
+                __builtin_nontemporal_store(vk[it], K_out + (size_t)p * ROW_U4 + c);
+                __builtin_nontemporal_store(vv[it], V_out + (size_t)p * ROW_U4 + c);
+            }
         }
     }
 }
@@ -72,15 +74,15 @@ hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, i
                           const int32_t* indices, const int64_t* d_offsets, int64_t total,
                           void* K_out, void* V_out, hipStream_t stream) {
     if (total == 0) return hipSuccess;
-    const int64_t blocks = (total + kRowsPerBlock - 1) / kRowsPerBlock;
+    const int64_t blocks = (total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         compact_kernel<16><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const uint4*)K, (const uint4*)V, n, indices, d_offsets, ctx->heads, total,
-            (uint4*)K_out, (uint4*)V_out);
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, ctx->plan.d_block_info, total,
+            (u32x4*)K_out, (u32x4*)V_out);
     } else {
         compact_kernel<32><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const uint4*)K, (const uint4*)V, n, indices, d_offsets, ctx->heads, total,
-            (uint4*)K_out, (uint4*)V_out);
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, ctx->plan.d_block_info, total,
+            (u32x4*)K_out, (u32x4*)V_out);
     }
     return hipGetLastError();
 }

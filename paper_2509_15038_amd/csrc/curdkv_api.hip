@@ -46,19 +46,32 @@ int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets
     }
     *total = offsets[heads];
     Plan& pl = ctx->plan;
-    const size_t bytes = (size_t)(heads + 1) * sizeof(int64_t);
-    if (pl.valid && std::memcmp(pl.cached.data(), offsets, bytes) == 0) return CURDKV_OK;
+    const size_t off_bytes = ((size_t)(heads + 1) * sizeof(int64_t) + 15) & ~(size_t)15;
+    const size_t cmp_bytes = (size_t)(heads + 1) * sizeof(int64_t);
+    if (pl.valid && std::memcmp(pl.cached.data(), offsets, cmp_bytes) == 0) return CURDKV_OK;
     if (pl.copy_pending) {                       // staging buffer may still be being read
         if (hipEventSynchronize(pl.copied) != hipSuccess) return CURDKV_ERR_HIP;
         pl.copy_pending = false;
     }
-    std::memcpy(pl.h_staging, offsets, bytes);
+    std::memcpy(pl.h_staging, offsets, cmp_bytes);
+    // head owning the first row of every gather block
+    const size_t blocks = (size_t)((*total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock);
+    BlockInfo* bi = reinterpret_cast<BlockInfo*>(pl.h_staging + off_bytes);
+    int h = 0;
+    for (size_t b = 0; b < blocks; ++b) {
+        const int64_t p = (int64_t)b * kCompactRowsPerBlock;
+        while (offsets[h + 1] <= p) ++h;
+        bi[b].head_end = offsets[h + 1];
+        bi[b].head = h;
+        bi[b].pad = 0;
+    }
+    const size_t bytes = off_bytes + blocks * sizeof(BlockInfo);
     pl.valid = false;
-    if (hipMemcpyAsync(pl.d_offsets, pl.h_staging, bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (hipMemcpyAsync(pl.d_buf, pl.h_staging, bytes, hipMemcpyHostToDevice, stream) != hipSuccess)
         return CURDKV_ERR_HIP;
     if (hipEventRecord(pl.copied, stream) != hipSuccess) return CURDKV_ERR_HIP;
     pl.copy_pending = true;
-    std::memcpy(pl.cached.data(), offsets, bytes);
+    std::memcpy(pl.cached.data(), offsets, cmp_bytes);
     pl.valid = true;
     return CURDKV_OK;
 }
@@ -67,7 +80,7 @@ void release(curdkv_ctx* ctx) {
     if (!ctx) return;
     if (ctx->d_G) (void)hipFree(ctx->d_G);
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
-    if (ctx->plan.d_offsets) (void)hipFree(ctx->plan.d_offsets);
+    if (ctx->plan.d_buf) (void)hipFree(ctx->plan.d_buf);
     if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
     if (ctx->plan.copied) (void)hipEventDestroy(ctx->plan.copied);
     delete ctx;
@@ -131,15 +144,20 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
     ctx->num_cu = cus > 0 ? cus : 256;
 
     const size_t g_bytes = (size_t)ctx->heads * ctx->g_elems_per_head * storage_bytes(cfg->dtype);
-    const size_t off_bytes = (size_t)(ctx->heads + 1) * sizeof(int64_t);
+    const size_t off_bytes = ((size_t)(ctx->heads + 1) * sizeof(int64_t) + 15) & ~(size_t)15;
+    ctx->plan.max_blocks = ((size_t)ctx->heads * (size_t)cfg->max_tokens + kCompactRowsPerBlock - 1) /
+                               kCompactRowsPerBlock + 1;
+    const size_t plan_bytes = off_bytes + ctx->plan.max_blocks * sizeof(BlockInfo);
     if (hipMalloc(&ctx->d_G, g_bytes) != hipSuccess ||
         hipMalloc((void**)&ctx->d_partial, (size_t)ctx->heads * kMaxBlocksPerHead * sizeof(float)) != hipSuccess ||
-        hipMalloc((void**)&ctx->plan.d_offsets, off_bytes) != hipSuccess ||
-        hipHostMalloc((void**)&ctx->plan.h_staging, off_bytes, hipHostMallocDefault) != hipSuccess) {
+        hipMalloc((void**)&ctx->plan.d_buf, plan_bytes) != hipSuccess ||
+        hipHostMalloc((void**)&ctx->plan.h_staging, plan_bytes, hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         release(ctx);
         return CURDKV_ERR_OOM;
     }
+    ctx->plan.d_offsets = reinterpret_cast<int64_t*>(ctx->plan.d_buf);
+    ctx->plan.d_block_info = reinterpret_cast<BlockInfo*>(ctx->plan.d_buf + off_bytes);
     if (hipEventCreateWithFlags(&ctx->plan.copied, hipEventDisableTiming) != hipSuccess) {
         release(ctx);
         return CURDKV_ERR_HIP;

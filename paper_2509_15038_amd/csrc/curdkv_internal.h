@@ -14,11 +14,23 @@ constexpr int kHeadDim = 128;          // d the kernels are written for
 constexpr int kColBlock = 32;          // sketch columns per MFMA tile (M of the 32x32 tile)
 constexpr int kMaxColBlocks = 4;       // r padded to 32, 64 or 128
 constexpr int kMaxBlocksPerHead = 64;  // partial sums kept per (layer, group)
-constexpr int kTileTokens = 32;        // tokens per wave tile (N of the 32x32 tile)
+constexpr int kTileTokens = 32;        // tokens per wave tile
+constexpr int kCompactRowsPerBlock = 128;  // output rows one gather block copies
 
-struct Plan {                          // device copy of the offsets, refreshed when they change
+struct BlockInfo {                     // for gather block b, whose first output row is b*128:
+    int64_t head_end;                  //   offsets[head + 1]
+    int32_t head;                      //   the head that owns that row
+    int32_t pad;
+};
+
+// Device copy of the offsets, refreshed when they change, followed by the
+// per-gather-block table.
+struct Plan {
     int64_t* d_offsets = nullptr;      // [heads + 1]
-    int64_t* h_staging = nullptr;      // pinned, [heads + 1]
+    BlockInfo* d_block_info = nullptr; // [max_blocks]
+    char* d_buf = nullptr;             // one allocation holding both
+    char* h_staging = nullptr;         // pinned, same layout
+    size_t max_blocks = 0;
     std::vector<int64_t> cached;       // what d_offsets holds (after the queued copy)
     bool valid = false;
     hipEvent_t copied = nullptr;       // recorded after the last staging -> device copy
