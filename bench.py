@@ -106,8 +106,9 @@ def main():
     Vo = torch.empty((max(total, 1), d), dtype=torch.bfloat16, device="cuda")
     ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed)
     s = cfg.n_sink
+    fused = cfg.dtype == "bf16" and cfg.r <= 64 and n <= 32768 and heads >= 128
 
-    def step(ev=None):
+    def step_calls(ev=None):
         if ev:
             ev[0].record()
         ctx.scores(Kd, Vd, n, scores)
@@ -120,25 +121,45 @@ def main():
         if ev:
             ev[3].record()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(evs[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    part_ms = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
-    step_ms_events = np.array([e[0].elapsed_time(e[3]) for e in evs])
-    avg = part_ms.mean(0)
+    def step_one_call(ev=None):
+        if ev:
+            ev[0].record()
+        ctx.compress(Kd, Vd, n, budgets, s, offsets, scores, indices, Ko, Vo)
+        if ev:
+            ev[3].record()
+
+    def timed(step):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(evs[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / args.steps, evs
 
     ab = algorithmic_bytes(cfg, budgets)
     kv_tokens = heads * n
+
+    # the three separate calls, with HIP events between them
+    ms_calls, evs = timed(step_calls)
+    part = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs]).mean(0)
+    calls = {"ms_per_step": ms_calls, "KV_tokens_per_s": kv_tokens / (ms_calls * 1e-3),
+             "path_GBps": ab["total"] / (ms_calls * 1e-3) / 1e9,
+             "frac_of_hbm_peak": ab["total"] / (ms_calls * 1e-3) / 1e9 / HBM_PEAK_GBS,
+             "ms": {"scores": float(part[0]), "select": float(part[1]), "compact": float(part[2])},
+             "GBps": {"scores": ab["scores"] / (part[0] * 1e-3) / 1e9,
+                      "select": ab["select"] / (part[1] * 1e-3) / 1e9,
+                      "compact": ab["compact"] / (part[2] * 1e-3) / 1e9}}
+
+    # the one-call entry point (one fused kernel at this shape): the headline
+    ms_per_step, evs = timed(step_one_call)
+    kern_ms = float(np.mean([e[0].elapsed_time(e[3]) for e in evs]))
     value = kv_tokens / (ms_per_step * 1e-3)
-    scores_gbs = ab["scores"] / (avg[0] * 1e-3) / 1e9
+    kern_gbs = ab["total"] / (kern_ms * 1e-3) / 1e9
     out = {
         "metric": "KV tokens scored+compacted/sec at 8B shape, 32k ctx; % of HBM peak",
         "value": value, "unit": "KV tokens/s (one token of one layer and KV head)",
@@ -147,19 +168,19 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} layers x {H} KV heads (GQA group {cfg.group}), "
                                f"n={n}, d={d}, r={cfg.r}, keep={keep:g} (k/head mean "
-                               f"{total / heads:.0f}), sinks={s}, bf16, resident in HBM",
+                               f"{total / heads:.0f}), sinks={s}, bf16, resident in HBM; "
+                               f"step = curdkv_compress (scores + select + compact)",
                    "layers": L, "kv_heads": H, "n": n, "d": d, "r": cfg.r, "keep": keep},
         "context_tokens_per_s": n / (ms_per_step * 1e-3),
         "path_GBps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
         "path_frac_of_hbm_peak": ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "ms_events": {"step_median": float(np.median(step_ms_events)),
-                      "scores": float(avg[0]), "select": float(avg[1]), "compact": float(avg[2])},
-        "GBps": {"scores": scores_gbs, "select": ab["select"] / (avg[1] * 1e-3) / 1e9,
-                 "compact": ab["compact"] / (avg[2] * 1e-3) / 1e9},
-        "roofline": {"bound": "hbm", "kernel": "curdkv_scores (project + row-norm^2 + combine + normalise)",
-                     "achieved": scores_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": scores_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": ab["scores"], "avg_ms": float(avg[0])},
+        "roofline": {"bound": "hbm",
+                     "kernel": "fused_kernel (whole path, one workgroup per head)" if fused else
+                               "curdkv_compress (scores, select and compact kernels)",
+                     "achieved": kern_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": kern_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": ab["total"], "avg_ms": kern_ms},
+        "three_calls": calls,
     }
 
     if not args.no_cpu_baseline:

@@ -127,6 +127,21 @@ int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                    const int32_t* indices, const int64_t* offsets,
                    void* K_out, void* V_out, void* stream);
 
+/* The whole of Algorithm 1 in one call: scores, selection and gather, with the
+ * results of curdkv_scores + curdkv_select + curdkv_compact (same arguments,
+ * same layouts; `scores` may be NULL when the caller does not want them, the
+ * library then uses a scratch buffer it allocates on first need).  When a head's
+ * scores fit in one compute unit's LDS (bf16, sketch_dim <= 64, n <= 32768) and
+ * there are at least half as many (layer, group) pairs as compute units, one
+ * fused kernel does everything with one workgroup per pair and the scores never
+ * pass through HBM between the steps; otherwise the three kernels of the
+ * separate calls are launched in order.  The normalising sum is taken in a
+ * different order in the two cases, so scores can differ in the last bits
+ * between them. */
+int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                    const int32_t* budgets, int32_t n_sink, const int64_t* offsets,
+                    float* scores, int32_t* indices, void* K_out, void* V_out, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* curdkv_strerror(int code);
 

@@ -22,7 +22,8 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 _DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
 
 EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
-           "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_strerror"]
+           "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
+           "curdkv_strerror"]
 
 
 class CurdkvConfig(C.Structure):
@@ -60,6 +61,7 @@ def lib() -> C.CDLL:
     L.curdkv_fold.argtypes = [vp, vp, i64, vp, vp]
     L.curdkv_select.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
     L.curdkv_compact.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
+    L.curdkv_compress.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
     L.curdkv_strerror.argtypes = [C.c_int]
     L.curdkv_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -169,3 +171,13 @@ class Context:
                                   offsets.ctypes.data, _ptr(K_out), _ptr(V_out), _stream(stream))
         if rc != OK:
             raise CurdkvError(rc, "curdkv_compact")
+
+    def compress(self, K, V, n: int, budgets: np.ndarray, n_sink: int, offsets: np.ndarray,
+                 scores, indices, K_out, V_out, stream=None):
+        assert budgets.dtype == np.int32 and offsets.dtype == np.int64
+        assert budgets.size == self.heads and offsets.size == self.heads + 1
+        rc = lib().curdkv_compress(self._h, _ptr(K), _ptr(V), int(n), budgets.ctypes.data,
+                                   int(n_sink), offsets.ctypes.data, _ptr(scores), _ptr(indices),
+                                   _ptr(K_out), _ptr(V_out), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_compress")

@@ -80,6 +80,7 @@ void release(curdkv_ctx* ctx) {
     if (!ctx) return;
     if (ctx->d_G) (void)hipFree(ctx->d_G);
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
+    if (ctx->d_scores_ws) (void)hipFree(ctx->d_scores_ws);
     if (ctx->plan.d_buf) (void)hipFree(ctx->plan.d_buf);
     if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
     if (ctx->plan.copied) (void)hipEventDestroy(ctx->plan.copied);
@@ -178,7 +179,8 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
             err = upload_sketch(ctx, l * cfg->kv_heads + h, G);
         }
     std::free(G);
-    if (err == CURDKV_OK && (configure_kernels(ctx) != hipSuccess || configure_select(ctx) != hipSuccess))
+    if (err == CURDKV_OK && (configure_kernels(ctx) != hipSuccess || configure_select(ctx) != hipSuccess ||
+                              configure_fused(ctx) != hipSuccess))
         err = CURDKV_ERR_HIP;
     if (err != CURDKV_OK) { release(ctx); return err; }
     *out = ctx;
@@ -248,6 +250,36 @@ int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, con
     if (!indices || !K_out || !V_out) return CURDKV_ERR_INVALID_ARG;
     return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out,
                           (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, const int32_t* budgets,
+                    int32_t n_sink, const int64_t* offsets, float* scores, int32_t* indices,
+                    void* K_out, void* V_out, void* stream) {
+    if (!ctx || !K || !V || !budgets || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0) return CURDKV_ERR_INVALID_ARG;
+    if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)K_out | (uintptr_t)V_out) & 15u) return CURDKV_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int64_t total = 0;
+    const int rc = sync_offsets(ctx, offsets, budgets, n, st, &total);
+    if (rc != CURDKV_OK) return rc;
+    if (total > 0 && (!indices || !K_out || !V_out)) return CURDKV_ERR_INVALID_ARG;
+    if (fused_applicable(ctx, n))
+        return launch_fused(ctx, K, V, n, n_sink, ctx->plan.d_offsets, scores, indices, K_out, V_out, st) == hipSuccess
+                   ? CURDKV_OK : CURDKV_ERR_HIP;
+    if (!scores) {
+        if (!ctx->d_scores_ws &&
+            hipMalloc((void**)&ctx->d_scores_ws, (size_t)ctx->heads * (size_t)ctx->cfg.max_tokens * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->d_scores_ws = nullptr;
+            return CURDKV_ERR_OOM;
+        }
+        scores = ctx->d_scores_ws;
+    }
+    if (launch_scores(ctx, K, V, n, scores, st) != hipSuccess) return CURDKV_ERR_HIP;
+    if (total == 0) return CURDKV_OK;
+    if (launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st) != hipSuccess) return CURDKV_ERR_HIP;
+    return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out, st) == hipSuccess
+               ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 
 }  // extern "C"

@@ -47,6 +47,7 @@ struct curdkv_ctx {
     size_t g_elems_per_head = 0;       // packed operand elements per (layer, group)
     void* d_G = nullptr;               // packed sketches, storage type
     float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
+    float* d_scores_ws = nullptr;      // [heads, max_tokens], allocated when curdkv_compress needs it
     int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes
     int num_cu = 0;
     curdkv::Plan plan;
@@ -73,5 +74,10 @@ hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, i
                           void* K_out, void* V_out, hipStream_t stream);
 hipError_t configure_kernels(curdkv_ctx* ctx);
 hipError_t configure_select(curdkv_ctx* ctx);
+hipError_t configure_fused(curdkv_ctx* ctx);
+bool fused_applicable(const curdkv_ctx* ctx, int64_t n);
+hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
+                        const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
+                        void* V_out, hipStream_t stream);
 
 }  // namespace curdkv

@@ -1,0 +1,173 @@
+// Fused kernel: the whole of Algorithm 1 for one (layer, group) per workgroup --
+// project, row-norm squared, combine, normalise, sinks + top-k, gather -- for
+// gfx950, bf16 storage, n <= 512 * KPT and sketch width <= 64.
+//
+// Why one workgroup per head: a head's n scores (128 KB at n = 32768) fit in one
+// CU's LDS, so they never have to travel through HBM between the steps, the sum
+// that normalises them is a plain workgroup reduction, and the selection reads
+// its keys from LDS.  Llama-3-8B / Mistral-7B caches have 32 x 8 = 256 KV heads,
+// one per CU of the MI355X.  The phases are:
+//   1. eight waves stream the head's K and V once (scan_device.h), scores -> LDS;
+//   2. workgroup sum in a fixed order, in double;
+//   3. scale, write the normalised scores out (optional), form the sort keys in
+//      registers; the LDS array is then free and becomes the index staging area;
+//   4. radix select + ordered compaction (select_device.h), indices -> LDS -> HBM;
+//   5. gather the chosen rows of K and V into the packed output, 16 bytes per
+//      lane, non-temporal.
+// All workgroups run phase 1 together, so HBM sees a pure read stream there and
+// a pure copy stream in phase 5.
+
+#include "scan_device.h"
+#include "select_device.h"
+
+namespace curdkv {
+
+constexpr int kFusedThreads = 512;
+constexpr int kFusedWaves = kFusedThreads / 64;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int CB, int KPT>
+__global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
+    const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
+    int32_t n, int32_t n_sink, const int64_t* __restrict__ offsets, float* __restrict__ scores_out,
+    int32_t* __restrict__ indices, u32x4* __restrict__ K_out, u32x4* __restrict__ V_out) {
+    extern __shared__ float sc[];                  // [n rounded up to 64]; later int32 stage[n]
+    __shared__ SelectShared<kFusedThreads, KPT> sm;
+    __shared__ float wsum[kFusedWaves];
+
+    const int head = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint4* Kh = K + (size_t)head * n * 16;   // 16 chunks of 16 bytes per row
+    const uint4* Vh = V + (size_t)head * n * 16;
+
+    // ---- 1. scores of the whole head into LDS ---------------------------------------
+    float acc;
+    {
+        SketchRegs<CB> G;
+        load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
+        const int64_t tiles = ((int64_t)n + kTileTokens - 1) / kTileTokens;
+        int64_t per_wave = (tiles + kFusedWaves - 1) / kFusedWaves;
+        per_wave += per_wave & 1;                  // whole pairs
+        const int64_t t_begin = (int64_t)wave * per_wave;
+        const int64_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
+        acc = scan_tiles<CB>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane);
+    }
+    // ---- 2. sum over the head ----------------------------------------------------------
+    acc = wave_sum(acc);
+    if (lane == 0) wsum[wave] = acc;
+    __syncthreads();
+    double tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < kFusedWaves; ++w) tot += (double)wsum[w];
+    const bool zero = !(tot > 0.0);
+    const float inv = zero ? 0.f : (float)(1.0 / tot);
+    const float uniform = (float)(1.0 / (double)n);
+
+    // ---- 3. normalise, write out, keys into registers ----------------------------------
+    uint32_t x[KPT];
+    float* so = scores_out ? scores_out + (size_t)head * n : nullptr;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        const int32_t j = it * kFusedThreads + tid;
+        float v = 0.f;
+        if (j < n) {
+            v = zero ? uniform : sc[j] * inv;
+            if (so) so[j] = v;
+        }
+        x[it] = order_key(v);
+    }
+    const int64_t o0 = offsets[head];
+    const int32_t k = (int32_t)(offsets[head + 1] - o0);
+    if (k <= 0) return;
+    __syncthreads();                               // sc[] has been read by everyone: reuse it
+
+    // ---- 4. selection ------------------------------------------------------------------
+    int32_t* stage = reinterpret_cast<int32_t*>(sc);
+    int32_t* out = indices + o0;
+    const int32_t s = n_sink < n ? n_sink : n;
+    select_core<kFusedThreads, KPT>(x, n, s, k, sm, stage, n, out);
+    for (int32_t p = tid; p < k; p += kFusedThreads) out[p] = stage[p];
+
+    // ---- 5. gather ---------------------------------------------------------------------
+    constexpr int kRowsPerIter = kFusedThreads / 16;      // 32 rows per instruction
+    constexpr int kIters = 4;
+    const int c = tid & 15, rsub = tid >> 4;
+    const u32x4* Kr = reinterpret_cast<const u32x4*>(Kh);
+    const u32x4* Vr = reinterpret_cast<const u32x4*>(Vh);
+    u32x4* Ko = K_out + (size_t)o0 * 16;
+    u32x4* Vo = V_out + (size_t)o0 * 16;
+    for (int32_t p0 = 0; p0 < k; p0 += kRowsPerIter * kIters) {
+        int32_t idx[kIters];
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int32_t p = p0 + it * kRowsPerIter + rsub;
+            idx[it] = stage[p < k ? p : k - 1];
+        }
+        u32x4 vk[kIters], vv[kIters];
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            vk[it] = __builtin_nontemporal_load(Kr + (size_t)idx[it] * 16 + c);
+            vv[it] = __builtin_nontemporal_load(Vr + (size_t)idx[it] * 16 + c);
+        }
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const int32_t p = p0 + it * kRowsPerIter + rsub;
+            if (p < k) {
+                __builtin_nontemporal_store(vk[it], Ko + (size_t)p * 16 + c);
+                __builtin_nontemporal_store(vv[it], Vo + (size_t)p * 16 + c);
+            }
+        }
+    }
+}
+
+template <int CB, int KPT>
+static hipError_t launch_one(const curdkv_ctx* ctx, const void* K, const void* V, int32_t n,
+                             int32_t n_sink, const int64_t* d_offsets, float* scores,
+                             int32_t* indices, void* K_out, void* V_out, hipStream_t stream) {
+    const size_t lds = (((size_t)n + 63) & ~(size_t)63) * 4;
+    fused_kernel<CB, KPT><<<dim3((unsigned)ctx->heads), kFusedThreads, lds, stream>>>(
+        (const uint4*)K, (const uint4*)V, (const uint4*)ctx->d_G, n, n_sink, d_offsets, scores,
+        indices, (u32x4*)K_out, (u32x4*)V_out);
+    return hipGetLastError();
+}
+
+template <int CB, int KPT>
+static hipError_t configure_one(int dyn) {
+    return hipFuncSetAttribute((const void*)fused_kernel<CB, KPT>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+}
+
+hipError_t configure_fused(curdkv_ctx* ctx) {
+    const int dyn = ctx->lds_limit - 16 * 1024;
+    if (dyn <= 48 * 1024) return hipSuccess;
+    hipError_t e;
+    if ((e = configure_one<2, 32>(dyn)) != hipSuccess) return e;
+    if ((e = configure_one<2, 64>(dyn)) != hipSuccess) return e;
+    if ((e = configure_one<4, 32>(dyn)) != hipSuccess) return e;
+    return configure_one<4, 64>(dyn);
+}
+
+// The fused kernel applies when a head's scores fit in LDS and there are enough
+// heads to occupy the GPU with one workgroup each.
+bool fused_applicable(const curdkv_ctx* ctx, int64_t n) {
+    if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return false;
+    if (n > 64 * kFusedThreads) return false;
+    const size_t lds = (((size_t)n + 63) & ~(size_t)63) * 4 + sizeof(SelectShared<kFusedThreads, 64>) + 1024;
+    if (lds > (size_t)ctx->lds_limit) return false;
+    return 2 * ctx->heads >= ctx->num_cu;
+}
+
+hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
+                        const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
+                        void* V_out, hipStream_t stream) {
+    const int32_t n32 = (int32_t)n;
+    const bool small = n <= 32 * kFusedThreads;
+    if (ctx->col_blocks == 1) {
+        return small ? launch_one<2, 32>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream)
+                     : launch_one<2, 64>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream);
+    }
+    return small ? launch_one<4, 32>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream)
+                 : launch_one<4, 64>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream);
+}
+
+}  // namespace curdkv

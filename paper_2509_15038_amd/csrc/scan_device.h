@@ -1,0 +1,189 @@
+// Device code of the bf16 scoring pass: Algorithm 1, lines "Project", "Compute
+// leverage scores" and "Combine scores", for gfx950.  Shared by the stand-alone
+// scoring kernel and the fused kernel.
+//
+// The projection is computed transposed, Y^T = G^T A^T (A = K_i or V_i), with
+// mfma_f32_16x16x32_bf16: G^T is the A operand (M = 16 sketch columns), a
+// sub-tile of 16 token rows is the B operand (N = 16 tokens).  A wave works
+// through a contiguous range of 32-token tiles in pairs (64 tokens); a tile is
+// two sub-tiles.  In a sub-tile lane L owns token L%16 and, at MFMA step s
+// (0..3), the 16 bytes holding d in [s*32 + (L/16)*8, +8): the four lanes of a
+// token read 64 contiguous bytes per load instruction and the wave reads whole
+// 256-byte rows over the four steps, which the memory system serves as well as
+// a fully coalesced stream.  The accumulator of lane L holds sketch coordinates
+// cb*16 + 4*(L/16) + {0..3} of token L%16, so the row-norm squared is a sum in
+// the lane plus exchanges between the four 16-lane rows, done with the gfx950
+// lane-swap instructions (no LDS round trip).  After the exchange every lane of
+// a token holds its score; lane row j keeps the score of sub-tile j of the pair,
+// so a pair ends with lane L holding the score of token 64*pair + L.  The
+// projected rows never leave registers, and scores go to LDS: a global store
+// inside the streaming loop costs several percent of the read bandwidth.
+#pragma once
+
+#include <type_traits>
+
+#include "curdkv_internal.h"
+
+namespace curdkv {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+union Chunk {           // 16 bytes of a token row: 8 bf16
+    uint4 u;
+    bf16x8 v;
+};
+
+struct TileRegs {       // one 32-token tile of K and of V as seen by a lane
+    Chunk k[2][4];
+    Chunk v[2][4];
+};
+
+template <int CB>       // CB = padded sketch width / 16
+struct SketchRegs {
+    bf16x8 g[CB][4];
+};
+
+template <int CB>
+__device__ __forceinline__ void load_sketch(SketchRegs<CB>& G, const uint4* __restrict__ Gp_head, int lane) {
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            Chunk c;
+            c.u = Gp_head[(cb * 4 + s) * 64 + lane];
+            G.g[cb][s] = c.v;
+        }
+}
+
+// a[32..63] <-> b[0..31]
+__device__ __forceinline__ void swap_halves(float& a, float& b) {
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+// odd 16-lane rows of a <-> even 16-lane rows of b
+__device__ __forceinline__ void swap_rows(float& a, float& b) {
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
+// lk, lv: per-lane partial sums of a token held by lanes t, t+16, t+32, t+48.
+// Returns (sum of the four lk) * (sum of the four lv) in all four lanes.
+__device__ __forceinline__ float combine_rows(float lk, float lv) {
+    swap_halves(lk, lv);                 // lk = [lk rows 0,1 | lv rows 0,1], lv = [lk rows 2,3 | lv rows 2,3]
+    float x = lk + lv;                   // rows: lk0+lk2, lk1+lk3, lv0+lv2, lv1+lv3
+    float y = x;
+    swap_rows(x, y);                     // x = rows 0,0,2,2 ; y = rows 1,1,3,3
+    float z = x + y;                     // rows: LK, LK, LV, LV
+    float w = z;
+    swap_halves(z, w);                   // z = LK everywhere, w = LV everywhere
+    return z * w;
+}
+
+// Scores tiles [t_begin, t_end) of one head; the score of token `row` is written
+// to lds_rows[row - row0].  t_begin must be even, and t_end even or equal to
+// ceil(n/32): tiles are handled in pairs and a missing second tile is taken to
+// lie beyond n.  Returns this lane's sum of
+// the scores it wrote.  Kh, Vh: the head's rows, 16 chunks of 16 bytes each.
+template <int CB>
+__device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4* __restrict__ Kh,
+                                            const uint4* __restrict__ Vh, int64_t n, int64_t t_begin,
+                                            int64_t t_end, float* lds_rows, int64_t row0, int lane) {
+    const int tok = lane & 15, q = lane >> 4;
+    float acc_sum = 0.f;
+    float pend = 0.f;                                           // this lane's score of the current pair
+
+    // CHECK = false is for tiles known to lie entirely below n: no clamping, no
+    // predicate, hence no branch, which keeps the steady-state loop one basic
+    // block so that the compiler's wait counts let loads stay in flight.
+    auto load_tile = [&](TileRegs& r, int64_t tile, auto check) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            int64_t row = tile * kTileTokens + t2 * 16 + tok;
+            if (decltype(check)::value) row = row < n ? row : n - 1;   // ragged tail: reload the last row
+            const uint4* kp = Kh + row * 16 + q;
+            const uint4* vp = Vh + row * 16 + q;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) r.v[t2][s].u = vp[s * 4];
+        }
+    };
+    auto compute_tile = [&](const TileRegs& r, int slot) {      // slot: 0 = first tile of the pair
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            f32x4 ak[CB], av[CB];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) { ak[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; av[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    ak[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.k[t2][s].v, ak[cb], 0, 0, 0);
+                    av[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.v[t2][s].v, av[cb], 0, 0, 0);
+                }
+            float lk = 0.f, lv = 0.f;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    lk = fmaf(ak[cb][e], ak[cb][e], lk);
+                    lv = fmaf(av[cb][e], av[cb][e], lv);
+                }
+            const float lkv = combine_rows(lk, lv);
+            pend = (q == slot * 2 + t2) ? lkv : pend;
+        }
+    };
+    auto store_pair = [&](int64_t tile, auto check) {           // lane L holds token tile*32 + L
+        const int64_t row = tile * kTileTokens + lane;
+        if (!decltype(check)::value || row < n) {
+            lds_rows[row - row0] = pend;
+            acc_sum += pend;
+        }
+    };
+    const std::true_type checked;
+    const std::false_type unchecked;
+
+    if (t_begin < t_end) {
+        TileRegs ra, rb;
+        int64_t t = t_begin;
+        // both buffers are always filled (a lone tile is simply loaded twice): a
+        // conditional load here would make every wait in the loop below pessimistic
+        load_tile(ra, t, checked);
+        load_tile(rb, t + 1 < t_end ? t + 1 : t, checked);
+        const int64_t full = n / kTileTokens;                   // tiles with all 32 rows below n
+        const int64_t t_steady = t_end < full ? t_end : full;
+        for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 are whole
+            compute_tile(ra, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(ra, t + 2, unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_tile(rb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(rb, t + 3, unchecked);
+            store_pair(t, unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (; t < t_end; t += 2) {                             // last one or two pairs
+            compute_tile(ra, 0);
+            if (t + 2 < t_end) load_tile(ra, t + 2, checked);
+            if (t + 1 < t_end) {
+                compute_tile(rb, 1);
+                if (t + 3 < t_end) load_tile(rb, t + 3, checked);
+            }
+            store_pair(t, checked);                             // an absent second tile lies beyond n
+        }
+    }
+    return acc_sum;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+}  // namespace curdkv

@@ -7,33 +7,19 @@
 // as the B operand (N = tokens).  In the accumulator layout a lane then owns
 // several sketch coordinates of ONE token (its column), so the row-norm squared
 // is a sum inside the lane plus one or two lane exchanges.  The projected rows
-// never leave registers.
+// never leave registers.  The bf16 inner loop lives in scan_device.h.
 
-#include <type_traits>
-
-#include "curdkv_internal.h"
+#include "scan_device.h"
 
 namespace curdkv {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-union Chunk {           // 16 bytes of a token row: 8 bf16
-    uint4 u;
-    bf16x8 v;
-};
 
 __device__ __forceinline__ float sum_sq(const f32x16& a) {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) s = fmaf(a[i], a[i], s);
     return s;
-}
-
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
-    return x;
 }
 
 // Sum the four wave totals of a 256-thread block in a fixed order and store it.
@@ -46,76 +32,23 @@ __device__ __forceinline__ void block_partial_store(float wave_total, float* dst
 }
 
 // ---------------------------------------------------------------------------
-// bf16 storage: mfma_f32_16x16x32_bf16.  A wave owns a contiguous range of
-// 32-token tiles and works through it in pairs (64 tokens); a tile is two
-// sub-tiles of 16 tokens.  In a sub-tile lane L owns token L%16 and, at MFMA
-// step s (0..3), the 16 bytes holding d in [s*32 + (L/16)*8, +8): the four lanes
-// of a token read 64 contiguous bytes per load instruction and the wave reads
-// whole 256-byte rows over the four steps, which the memory system serves as
-// well as a fully coalesced stream.  The accumulator of lane L holds sketch
-// coordinates cb*16 + 4*(L/16) + {0..3} of token L%16, so the row-norm squared
-// is a sum in the lane plus exchanges between the four 16-lane rows, done with
-// the gfx950 lane-swap instructions (no LDS round trip).  After the exchange
-// every lane of a token holds its score; lane row j keeps the score of sub-tile
-// j of the pair, so a pair ends in ONE coalesced 256-byte store of 64 scores.
-// Loads of a tile are issued as soon as the MFMAs that used its buffer are
-// done (two register buffers).  CB = padded sketch width / 16.
+// bf16 storage.  Each wave scores a contiguous range of tiles (scan_device.h),
+// collecting the scores in its own slice of LDS, and writes them out in one
+// burst per kStageTiles tiles: no global store sits inside the streaming loop.
 // ---------------------------------------------------------------------------
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-
-struct TileRegs {
-    Chunk k[2][4];
-    Chunk v[2][4];
-};
-
-// a[32..63] <-> b[0..31]
-__device__ __forceinline__ void swap_halves(float& a, float& b) {
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    a = __uint_as_float(r[0]);
-    b = __uint_as_float(r[1]);
-}
-// odd 16-lane rows of a <-> even 16-lane rows of b
-__device__ __forceinline__ void swap_rows(float& a, float& b) {
-    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    a = __uint_as_float(r[0]);
-    b = __uint_as_float(r[1]);
-}
-
-// lk, lv: per-lane partial sums of a token held by lanes t, t+16, t+32, t+48.
-// Returns (sum of the four lk) * (sum of the four lv) in all four lanes.
-__device__ __forceinline__ float combine_rows(float lk, float lv) {
-    swap_halves(lk, lv);                 // lk = [lk rows 0,1 | lv rows 0,1], lv = [lk rows 2,3 | lv rows 2,3]
-    float x = lk + lv;                   // rows: lk0+lk2, lk1+lk3, lv0+lv2, lv1+lv3
-    float y = x;
-    swap_rows(x, y);                     // x = rows 0,0,2,2 ; y = rows 1,1,3,3
-    float z = x + y;                     // rows: LK, LK, LV, LV
-    float w = z;
-    swap_halves(z, w);                   // z = LK everywhere, w = LV everywhere
-    return z * w;
-}
+constexpr int kStageTiles = 64;     // tiles (of 32 tokens) a wave collects between bursts: 8 KB
 
 template <int CB>
 __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
+    __shared__ float stage[4][kStageTiles * kTileTokens];
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tok = lane & 15, q = lane >> 4;
 
-    bf16x8 g[CB][4];
-    {
-        const uint4* gp = Gp + (size_t)head * (CB * 4 * 64) + lane;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                Chunk c;
-                c.u = gp[(cb * 4 + s) * 64];
-                g[cb][s] = c.v;
-            }
-    }
+    SketchRegs<CB> G;
+    load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
 
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
     const int64_t waves_per_head = (int64_t)blocks_per_head * 4;
@@ -127,88 +60,12 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* Vh = V + (size_t)head * n * 16;
     float* sh = scores + (size_t)head * n;
     float acc_sum = 0.f;
-    float pend = 0.f;                                           // this lane's score of the current pair
-
-    // CHECK = false is for tiles known to lie entirely below n: no clamping, no
-    // predicate, hence no branch, which keeps the steady-state loop one basic
-    // block so that the compiler's wait counts let loads stay in flight.
-    auto load_tile = [&](TileRegs& r, int64_t tile, auto check) {
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-            int64_t row = tile * kTileTokens + t2 * 16 + tok;
-            if (decltype(check)::value) row = row < n ? row : n - 1;   // ragged tail: reload the last row
-            const uint4* kp = Kh + row * 16 + q;
-            const uint4* vp = Vh + row * 16 + q;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) r.v[t2][s].u = vp[s * 4];
-        }
-    };
-    auto compute_tile = [&](const TileRegs& r, int slot) {      // slot: 0 = first tile of the pair
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-            f32x4 ak[CB], av[CB];
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) { ak[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; av[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) {
-                    ak[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g[cb][s], r.k[t2][s].v, ak[cb], 0, 0, 0);
-                    av[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g[cb][s], r.v[t2][s].v, av[cb], 0, 0, 0);
-                }
-            float lk = 0.f, lv = 0.f;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    lk = fmaf(ak[cb][e], ak[cb][e], lk);
-                    lv = fmaf(av[cb][e], av[cb][e], lv);
-                }
-            const float lkv = combine_rows(lk, lv);
-            pend = (q == slot * 2 + t2) ? lkv : pend;
-        }
-    };
-    auto store_pair = [&](int64_t tile, auto check) {           // lane L holds token tile*32 + L
-        const int64_t row = tile * kTileTokens + lane;
-        if (!decltype(check)::value || row < n) {
-            sh[row] = pend;
-            acc_sum += pend;
-        }
-    };
-    const std::true_type checked;
-    const std::false_type unchecked;
-
-    if (t_begin < t_end) {
-        TileRegs ra, rb;
-        int64_t t = t_begin;
-        // both buffers are always filled (a lone tile is simply loaded twice): a
-        // conditional load here would make every wait in the loop below pessimistic
-        load_tile(ra, t, checked);
-        load_tile(rb, t + 1 < t_end ? t + 1 : t, checked);
-        const int64_t full = n / kTileTokens;                   // tiles with all 32 rows below n
-        const int64_t t_steady = t_end < full ? t_end : full;
-        for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 are whole
-            compute_tile(ra, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(ra, t + 2, unchecked);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_tile(rb, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(rb, t + 3, unchecked);
-            store_pair(t, unchecked);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        for (; t < t_end; t += 2) {                             // last one or two pairs
-            compute_tile(ra, 0);
-            if (t + 2 < t_end) load_tile(ra, t + 2, checked);
-            if (t + 1 < t_end) {
-                compute_tile(rb, 1);
-                if (t + 3 < t_end) load_tile(rb, t + 3, checked);
-            }
-            store_pair(t, checked);                             // an absent second tile lies beyond n
-        }
+    for (int64_t seg = t_begin; seg < t_end; seg += kStageTiles) {
+        const int64_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
+        const int64_t r0 = seg * kTileTokens;
+        acc_sum += scan_tiles<CB>(G, Kh, Vh, n, seg, seg_end, stage[wave], r0, lane);
+        const int64_t r1 = seg_end * kTileTokens < n ? seg_end * kTileTokens : n;
+        for (int64_t r = r0 + lane; r < r1; r += 64) sh[r] = stage[wave][r - r0];
     }
     block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
 }

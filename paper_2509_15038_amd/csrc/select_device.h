@@ -1,0 +1,204 @@
+// Device code of the per-head selection: Algorithm 1, lines "Preserve first s
+// tokens as sink indices", "Select top-(k-s) indices from l[s:]" and "Combine",
+// for gfx950.  Shared by the stand-alone selection kernel and the fused kernel.
+//
+// A workgroup of THREADS threads handles one (layer, group) with n <= THREADS*KPT.
+// Thread t holds the order-preserving 32-bit keys of tokens t, t + THREADS,
+// t + 2*THREADS, ... in registers for the whole selection, so every pass is
+// straight-line code with no loads.  A most-significant-digit radix select finds
+// the key T of the (k-s)-th largest candidate and how many keys equal to T are
+// still needed; an ordered compaction then lists, in ascending token order, the
+// sinks, every candidate above T and the first `need` candidates equal to T,
+// which realises "larger score first, then smaller index" exactly.
+//
+// The radix digits are taken from (key - kmin), starting at the highest bit in
+// which the head's keys differ at all.  Scores of one head span a few binades,
+// so digits taken from the raw bit pattern would pile almost every key into two
+// or three bins and serialise the LDS atomics; relative to the head's own range
+// the first digit already spreads the keys over up to 256 bins.
+//
+// The selected indices are collected in an LDS staging array (positions come
+// from an exclusive scan of per-(row, wave) counts, a row being THREADS
+// consecutive tokens), so that the caller can write them out, or gather by them,
+// with coalesced accesses.
+#pragma once
+
+#include "curdkv_internal.h"
+
+namespace curdkv {
+
+constexpr int kHistRep = 8;                       // replicated bins to thin out LDS atomic collisions
+
+__device__ __forceinline__ uint32_t order_key(float x) {
+    x = x + 0.0f;                                 // -0 -> +0
+    const uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+template <int THREADS, int KPT>
+struct SelectShared {
+    static constexpr int kWaves = THREADS / 64;
+    uint32_t hist[256 * kHistRep];
+    uint32_t bin_count[256];
+    uint32_t cnt[KPT * kWaves];                   // low 16 bits: keys above T, high 16: keys equal to T
+    uint32_t wave_a[kWaves], wave_b[kWaves];
+    uint32_t digit, want;
+};
+
+// x[it]: key of token it*THREADS + tid (any value for tokens >= n).  Writes the k
+// selected token indices, ascending, to stage[0..k) (positions >= cap go straight
+// to out_global instead).  All threads of the workgroup must call it; it ends
+// with a barrier, after which stage[] is complete.  0 <= k <= n, 0 <= s <= n,
+// n <= THREADS*KPT < 65536.
+template <int THREADS, int KPT>
+__device__ __forceinline__ void select_core(uint32_t (&x)[KPT], int32_t n, int32_t s, int32_t k,
+                                            SelectShared<THREADS, KPT>& sm, int32_t* stage,
+                                            int32_t cap, int32_t* out_global) {
+    constexpr int kWaves = THREADS / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    auto put = [&](uint32_t pos, int32_t j) {
+        if (pos < (uint32_t)cap) stage[pos] = j; else out_global[pos] = j;
+    };
+
+    const int32_t sinks = s < k ? s : k;           // budget inside the sink block: tokens 0..k-1
+    for (int32_t j = tid; j < sinks; j += THREADS) put(j, j);
+    const int32_t m = k - s;                       // picks among tokens [s, n)
+    const uint32_t span = (uint32_t)(n - s);
+    if (m <= 0) { __syncthreads(); return; }
+    if ((uint32_t)m >= span) {                     // everything is kept
+        for (int32_t j = s + tid; j < n; j += THREADS) put(j, j);
+        __syncthreads();
+        return;
+    }
+
+    // ---- range [kmin, kmax] of the candidates -----------------------------------
+    const uint32_t jt = (uint32_t)(tid - s);       // token - s of row 0, wraps for sinks
+    auto cand = [&](int it) -> bool { return jt + (uint32_t)(it * THREADS) < span; };
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it)
+        if (cand(it)) { kmin = x[it] < kmin ? x[it] : kmin; kmax = x[it] > kmax ? x[it] : kmax; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t a = __shfl_xor(kmin, off, 64), b = __shfl_xor(kmax, off, 64);
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+    if (lane == 0) { sm.wave_a[wave] = kmin; sm.wave_b[wave] = kmax; }
+    for (int i = tid; i < 256 * kHistRep; i += THREADS) sm.hist[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        kmin = sm.wave_a[w] < kmin ? sm.wave_a[w] : kmin;
+        kmax = sm.wave_b[w] > kmax ? sm.wave_b[w] : kmax;
+    }
+    // From here on x = key - kmin for candidates and all-ones for everything else
+    // (sinks, tokens beyond n).  Scores are non-negative, so a candidate's x stays
+    // below 2^31 and the all-ones value never matches a prefix or the threshold:
+    // the passes below need no per-token candidate test.
+    constexpr uint32_t kNotCand = 0xFFFFFFFFu;
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) x[it] = cand(it) ? x[it] - kmin : kNotCand;
+
+    // ---- radix select on x: T = the m-th largest among the candidates ----------------
+    const uint32_t range = kmax - kmin;
+    int rem = range ? 32 - __clz(range) : 0;       // bits of x not yet decided
+    rem = rem > 31 ? 31 : rem;                     // only reachable with negative scores (not supported)
+    uint32_t fixed = 0;                            // decided high part: x >> rem
+    uint32_t want = (uint32_t)m;
+    uint32_t* myhist = sm.hist + (lane & (kHistRep - 1));
+    while (rem > 0) {
+        const int w = rem < 8 ? rem : 8;
+        const int shift = rem - w;
+        const uint32_t dmask = (1u << w) - 1u;
+#pragma unroll
+        for (int it = 0; it < KPT; ++it)
+            if ((x[it] >> rem) == fixed)
+                atomicAdd(&myhist[((x[it] >> shift) & dmask) * kHistRep], 1u);
+        __syncthreads();
+        for (int b = tid; b < 256; b += THREADS) {
+            uint32_t c = 0;
+#pragma unroll
+            for (int r = 0; r < kHistRep; ++r) { c += sm.hist[b * kHistRep + r]; sm.hist[b * kHistRep + r] = 0; }
+            sm.bin_count[b] = c;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane L looks at bins 255-4L .. 252-4L (descending); find the bin where the
+            // count from the top reaches `want`
+            uint32_t c[4], tot = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { c[i] = sm.bin_count[255 - 4 * lane - i]; tot += c[i]; }
+            uint32_t incl = tot;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += t;
+            }
+            uint32_t run = incl - tot;             // keys in higher bins
+            if (run < want && want <= incl) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (want <= run + c[i]) { sm.digit = 255 - 4 * lane - i; sm.want = want - run; break; }
+                    run += c[i];
+                }
+            }
+        }
+        __syncthreads();
+        fixed = (fixed << w) | sm.digit;
+        want = sm.want;
+        rem = shift;
+        // digit/want are next written after two more barriers; the histogram is already clear
+    }
+    const uint32_t T = fixed;                      // in x space
+    const uint32_t need = want;                    // keys equal to T still to be kept (>= 1)
+
+    // ---- ordered compaction: token order is (row it, wave, lane) ----------------------
+    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    const uint32_t above = kNotCand - 1u - T;      // T < x < all-ones  <=>  x - T - 1 < above
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        const uint64_t bg = __ballot(x[it] - T - 1u < above), be = __ballot(x[it] == T);
+        if (lane == 0) sm.cnt[it * kWaves + wave] = (uint32_t)__popcll(bg) | ((uint32_t)__popcll(be) << 16);
+    }
+    __syncthreads();
+    if (wave == 0) {                               // exclusive scan of cnt[] in index order
+        constexpr int kPer = (KPT * kWaves + 63) / 64;
+        uint32_t v[kPer], tot = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = lane * kPer + i;
+            v[i] = e < KPT * kWaves ? sm.cnt[e] : 0u;
+            tot += v[i];
+        }
+        uint32_t incl = tot;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        uint32_t run = incl - tot;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int e = lane * kPer + i;
+            if (e < KPT * kWaves) sm.cnt[e] = run;
+            run += v[i];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < KPT; ++it) {
+        const uint32_t base = sm.cnt[it * kWaves + wave];
+        const bool g = x[it] - T - 1u < above, e = x[it] == T;
+        const uint64_t bg = __ballot(g), be = __ballot(e);
+        const uint32_t pg = (base & 0xFFFFu) + (uint32_t)__popcll(bg & lt_mask);
+        const uint32_t pe = (base >> 16) + (uint32_t)__popcll(be & lt_mask);
+        // positions stay below k by construction; the comparison keeps a write inside
+        // the group's slice whatever the keys were
+        const uint32_t pos = (uint32_t)s + pg + (pe < need ? pe : need);
+        if ((g || (e && pe < need)) && pos < (uint32_t)k) put(pos, it * THREADS + tid);
+    }
+    __syncthreads();
+}
+
+}  // namespace curdkv

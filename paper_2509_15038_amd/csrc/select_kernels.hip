@@ -1,40 +1,29 @@
-// Selection kernel: Algorithm 1, lines "Preserve first s tokens as sink
+// Selection kernels: Algorithm 1, lines "Preserve first s tokens as sink
 // indices", "Select top-(k-s) indices from l[s:]" and "Combine", for gfx950.
-//
-// One 1024-thread workgroup per (layer, group).  The scores are turned into
-// order-preserving 32-bit keys and, when they fit, held in LDS for the whole
-// kernel.  A most-significant-digit radix select (four 8-bit digits) finds the
-// key T of the (k-s)-th largest candidate and how many keys equal to T are
-// still needed; an ordered compaction then writes, in ascending token order,
-// the sinks, every candidate above T, and the first `need` candidates equal to
-// T.  That realises "larger score first, then smaller index" exactly.
+// One 1024-thread workgroup per (layer, group).  The method is described in
+// select_device.h; this file holds the kernels and their launcher.
 
-#include "curdkv_internal.h"
+#include "select_device.h"
 
 namespace curdkv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kHistRep = 8;                       // replicated bins to thin out LDS atomic collisions
-constexpr int kSelFixedLds = 256 * kHistRep * 4;  // histogram bytes in dynamic LDS
+constexpr int kSelFixedLds = 256 * kHistRep * 4;  // histogram bytes in the streaming kernel's dynamic LDS
 
-__device__ __forceinline__ uint32_t order_key(float x) {
-    x = x + 0.0f;                                 // -0 -> +0
-    const uint32_t b = __float_as_uint(x);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
-
-template <bool LDS_KEYS>
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores,
+// ---------------------------------------------------------------------------
+// Streaming variant for n too large for the register-resident one: every pass
+// re-reads the head's scores from memory (they sit in L2 / Infinity Cache).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float* __restrict__ scores,
                                                              int64_t n, int32_t n_sink,
                                                              const int64_t* __restrict__ offsets,
                                                              int32_t* __restrict__ indices) {
     extern __shared__ uint32_t dyn[];
     uint32_t* hist = dyn;                         // [256][kHistRep]
-    uint32_t* keys = dyn + 256 * kHistRep;        // [n] when LDS_KEYS
     __shared__ uint32_t bin_count[256];
     __shared__ uint32_t sh_digit, sh_want;
-    __shared__ uint32_t wave_gt[kSelWaves], wave_eq[kSelWaves];
+    __shared__ uint32_t wave_a[kSelWaves], wave_b[kSelWaves];
 
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,42 +45,62 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         return;
     }
 
-    if (LDS_KEYS) {
-        for (int64_t j = tid; j < n; j += kSelThreads) keys[j] = order_key(sc[j]);
+    // ---- the range [kmin, kmax] of the candidates --------------------------------
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+    {
+        const int64_t iters = (n + kSelThreads - 1) / kSelThreads;
+        for (int64_t it = 0; it < iters; it += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t j = (it + u) * kSelThreads + tid;
+                v[u] = j < n ? sc[j] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t j = (it + u) * kSelThreads + tid;
+                if (j < n) {
+                    const uint32_t key = order_key(v[u]);
+                    if (j >= s) { kmin = key < kmin ? key : kmin; kmax = key > kmax ? key : kmax; }
+                }
+            }
+        }
     }
-    auto key_at = [&](int64_t j) -> uint32_t { return LDS_KEYS ? keys[j] : order_key(sc[j]); };
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t a = __shfl_xor(kmin, off, 64), b = __shfl_xor(kmax, off, 64);
+        kmin = a < kmin ? a : kmin;
+        kmax = b > kmax ? b : kmax;
+    }
+    if (lane == 0) { wave_a[wave] = kmin; wave_b[wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+        kmin = wave_a[w] < kmin ? wave_a[w] : kmin;
+        kmax = wave_b[w] > kmax ? wave_b[w] : kmax;
+    }
+    auto key_at = [&](int64_t j) -> uint32_t { return order_key(sc[j]); };
 
-    // ---- radix select: T = the m-th largest key among tokens [s, n) ----------
-    uint32_t prefix = 0, mask = 0, want = (uint32_t)m;
+    // ---- radix select on x = key - kmin: T = the m-th largest among tokens [s, n) ----
+    const uint32_t range = kmax - kmin;
+    int rem = range ? 32 - __clz(range) : 0;       // bits of x not yet decided
+    uint32_t fixed = 0;                            // decided high part: x >> rem
+    uint32_t want = (uint32_t)m;
     const int64_t span = n - s;
     const int64_t iters = (span + kSelThreads - 1) / kSelThreads;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
+    bool first = true;
+    while (rem > 0) {
+        const int w = rem < 8 ? rem : 8;
+        const int shift = rem - w;
+        const uint32_t dmask = (1u << w) - 1u;
         for (int i = tid; i < 256 * kHistRep; i += kSelThreads) hist[i] = 0;
-        __syncthreads();                           // also orders the key stores above
+        __syncthreads();
         for (int64_t it = 0; it < iters; ++it) {
             const int64_t j = s + it * kSelThreads + tid;
-            bool valid = j < n;
-            uint32_t digit = 0;
-            if (valid) {
-                const uint32_t key = key_at(j);
-                valid = (key & mask) == prefix;
-                digit = (key >> shift) & 255u;
-            }
-            if (pass == 0) {
-                // leading digits are few (sign and high exponent bits): count them per
-                // wave with ballots, one LDS atomic per distinct digit
-                uint64_t active = __ballot(valid);
-                while (active) {
-                    const int leader = __ffsll((unsigned long long)active) - 1;
-                    const uint32_t d0 = __shfl(digit, leader, 64);
-                    const uint64_t same = __ballot(valid && digit == d0);
-                    if (lane == leader) atomicAdd(&hist[d0 * kHistRep + (wave & (kHistRep - 1))], (uint32_t)__popcll(same));
-                    if (digit == d0) valid = false;
-                    active &= ~same;
-                }
-            } else if (valid) {
-                atomicAdd(&hist[digit * kHistRep + (lane & (kHistRep - 1))], 1u);
+            if (j < n) {
+                const uint32_t x = key_at(j) - kmin;
+                if (first || (x >> rem) == fixed)
+                    atomicAdd(&hist[((x >> shift) & dmask) * kHistRep + (lane & (kHistRep - 1))], 1u);
             }
         }
         __syncthreads();
@@ -124,12 +133,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             }
         }
         __syncthreads();
-        prefix |= sh_digit << shift;
-        mask |= 255u << shift;
+        fixed = (fixed << w) | sh_digit;
         want = sh_want;
+        rem = shift;
+        first = false;
         __syncthreads();                           // sh_* are rewritten next pass
     }
-    const uint32_t T = prefix;
+    const uint32_t T = kmin + fixed;
     const uint32_t need = want;                    // keys equal to T still to be kept (>= 1)
 
     // ---- ordered compaction ----------------------------------------------------
@@ -151,10 +161,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         cg += __shfl_xor(cg, off, 64);
         ce += __shfl_xor(ce, off, 64);
     }
-    if (lane == 0) { wave_gt[wave] = cg; wave_eq[wave] = ce; }
+    __syncthreads();                               // wave_a / wave_b held the key range
+    if (lane == 0) { wave_a[wave] = cg; wave_b[wave] = ce; }
     __syncthreads();
     uint32_t gt_before = 0, eq_before = 0;
-    for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
+    for (int w = 0; w < wave; ++w) { gt_before += wave_a[w]; eq_before += wave_b[w]; }
 
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     for (int64_t jb = j0; jb < j1; jb += 64) {
@@ -177,26 +188,79 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
 }
 
-static size_t select_lds_bytes(int64_t n) { return (size_t)kSelFixedLds + (size_t)n * 4; }
-constexpr size_t kSelStaticLds = 2048;   // bin counts, flags and wave counters, rounded up
+// ---------------------------------------------------------------------------
+// Register-resident variant (select_device.h) for n <= 1024 * KPT.  The chosen
+// indices are collected in LDS and written out coalesced.
+// ---------------------------------------------------------------------------
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void select_reg_kernel(const float* __restrict__ scores,
+                                                                 int32_t n, int32_t n_sink,
+                                                                 const int64_t* __restrict__ offsets,
+                                                                 int32_t* __restrict__ indices, int32_t cap) {
+    extern __shared__ int32_t stage[];             // [cap]
+    __shared__ SelectShared<kSelThreads, KPT> sm;
+    const int head = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int64_t o0 = offsets[head];
+    const int32_t k = (int32_t)(offsets[head + 1] - o0);
+    if (k <= 0) return;
+    int32_t* out = indices + o0;
+    const float* sc = scores + (size_t)head * n;
+    const int32_t s = n_sink < n ? n_sink : n;
+
+    uint32_t x[KPT];
+    {
+        float v[KPT];
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) {
+            const int32_t j = it * kSelThreads + tid;
+            v[it] = j < n ? sc[j] : 0.f;
+        }
+#pragma unroll
+        for (int it = 0; it < KPT; ++it) x[it] = order_key(v[it]);
+    }
+    select_core<kSelThreads, KPT>(x, n, s, k, sm, stage, cap, out);
+    const int32_t staged = k < cap ? k : cap;
+    for (int32_t p = tid; p < staged; p += kSelThreads) out[p] = stage[p];
+}
+
+template <int KPT>
+static hipError_t launch_reg(const curdkv_ctx* ctx, const float* scores, int32_t n, int32_t n_sink,
+                             const int64_t* d_offsets, int32_t* indices, hipStream_t stream) {
+    const size_t fixed = sizeof(SelectShared<kSelThreads, KPT>) + 256;
+    int64_t cap = ((int64_t)ctx->lds_limit - (int64_t)fixed) / 4;
+    if (cap > n) cap = n;
+    if (cap < 0) cap = 0;
+    select_reg_kernel<KPT><<<dim3((unsigned)ctx->heads), kSelThreads, (size_t)cap * 4, stream>>>(
+        scores, n, n_sink, d_offsets, indices, (int32_t)cap);
+    return hipGetLastError();
+}
 
 hipError_t configure_select(curdkv_ctx* ctx) {
-    const int dyn = ctx->lds_limit - (int)kSelStaticLds;
+    const int dyn = ctx->lds_limit - 16 * 1024;
     if (dyn <= 48 * 1024) return hipSuccess;
-    return hipFuncSetAttribute((const void*)select_kernel<true>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+    hipError_t e;
+    e = hipFuncSetAttribute((const void*)select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)select_reg_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)select_reg_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)select_reg_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)select_reg_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
 }
 
 hipError_t launch_select(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t n_sink,
                          const int64_t* d_offsets, int32_t* indices, hipStream_t stream) {
-    // static LDS of the kernel: bin_count + flags + wave counters
-    const bool fits = select_lds_bytes(n) + kSelStaticLds <= (size_t)ctx->lds_limit;
-    if (fits) {
-        const size_t lds = select_lds_bytes(n);
-        select_kernel<true><<<dim3((unsigned)ctx->heads), kSelThreads, lds, stream>>>(scores, n, n_sink, d_offsets, indices);
-    } else {
-        select_kernel<false><<<dim3((unsigned)ctx->heads), kSelThreads, kSelFixedLds, stream>>>(scores, n, n_sink, d_offsets, indices);
-    }
+    const int32_t n32 = (int32_t)n;
+    if (n <= 4 * kSelThreads) return launch_reg<4>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    if (n <= 8 * kSelThreads) return launch_reg<8>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    select_stream_kernel<<<dim3((unsigned)ctx->heads), kSelThreads, kSelFixedLds, stream>>>(
+        scores, n, n_sink, d_offsets, indices);
     return hipGetLastError();
 }
 

@@ -26,8 +26,10 @@ def to_host(t, dtype: str) -> np.ndarray:
     return t.cpu().numpy()
 
 
-def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, dtype: str):
-    """scores -> select -> compact through the C ABI.  Returns device tensors."""
+def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, dtype: str,
+             one_call: bool = False):
+    """scores -> select -> compact through the C ABI (or the one-call entry point,
+    which picks the fused kernel when it applies).  Returns device tensors."""
     import torch
     heads = ctx.heads
     offsets = wl.offsets_for(budgets)
@@ -37,9 +39,12 @@ def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, d
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     Ko = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
     Vo = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
-    ctx.scores(Kd, Vd, n, scores)
-    ctx.select(scores, n, budgets, n_sink, offsets, indices)
-    ctx.compact(Kd, Vd, n, indices, offsets, Ko, Vo)
+    if one_call:
+        ctx.compress(Kd, Vd, n, budgets, n_sink, offsets, scores, indices, Ko, Vo)
+    else:
+        ctx.scores(Kd, Vd, n, scores)
+        ctx.select(scores, n, budgets, n_sink, offsets, indices)
+        ctx.compact(Kd, Vd, n, indices, offsets, Ko, Vo)
     torch.cuda.synchronize()
     return scores, indices[:total], Ko[:total], Vo[:total], offsets
 
@@ -81,7 +86,8 @@ def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="
     return rel, ndiff
 
 
-def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None):
+def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None,
+                  one_call: bool = False):
     """Whole path on a host cache, every head compared with the oracle."""
     s = cfg.n_sink if n_sink is None else n_sink
     if K is None:
@@ -90,7 +96,7 @@ def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=No
     Kd, Vd = to_device(K, cfg.dtype), to_device(V, cfg.dtype)
     worst, ndiff = 0.0, 0
     with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
-        sc, idx, Ko, Vo, off = run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype)
+        sc, idx, Ko, Vo, off = run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype, one_call)
         sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
         Ko_h, Vo_h = to_host(Ko, cfg.dtype), to_host(Vo, cfg.dtype)
         for l in range(L):

@@ -24,7 +24,7 @@ def _announce(request):
     yield
 
 
-def _full(cfg, keeps, sample, gu):
+def _full(cfg, keeps, sample, gu, one_call=False):
     import torch
     L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
     heads = L * H
@@ -33,7 +33,7 @@ def _full(cfg, keeps, sample, gu):
         for keep in keeps:
             budgets = wl.budgets_for(cfg, keep)
             print(f"  {cfg.name} n={n} keep={keep} total rows={int(budgets.sum())}", flush=True)
-            sc, idx, Ko, Vo, off = gu.run_path(ctx, Kd, Vd, n, budgets, cfg.n_sink, cfg.dtype)
+            sc, idx, Ko, Vo, off = gu.run_path(ctx, Kd, Vd, n, budgets, cfg.n_sink, cfg.dtype, one_call)
             # ---- every group: invariants ------------------------------------------
             sums = sc.double().sum(1).cpu().numpy()
             assert np.allclose(sums, 1.0, atol=1e-4), "scores do not sum to one"
@@ -89,6 +89,14 @@ def gu():
 
 def test_c3_full_llama_32k_all_budgets(gu):
     _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu)
+
+
+def test_c3_full_one_call_fused(gu):
+    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu, one_call=True)
+
+
+def test_c4_full_one_call_fused(gu):
+    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu, one_call=True)
 
 
 def test_c4_full_mistral_32k_prefix(gu):

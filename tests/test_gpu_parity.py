@@ -144,6 +144,66 @@ def test_select_large_n_streaming_ties(gu):
         assert np.array_equal(idx[off[h]:off[h + 1]], want), h
 
 
+# ---- the one-call entry point; with >= 128 heads it runs the fused kernel ------------
+
+@pytest.mark.parametrize("keep", [0.10, 0.50])
+def test_one_call_fused_c3_shape(gu, keep):
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=2000 + 17)        # 128 heads, ragged n
+    gu.run_and_check(cfg, wl.budgets_for(cfg, keep), one_call=True)
+
+
+def test_one_call_fused_long_heads(gu):
+    cfg = wl.scaled(wl.CONFIGS["c4"], layers=16, n=16384 + 2048 + 33)  # second key-count variant
+    gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True)
+
+
+@pytest.mark.parametrize("r", [20, 32, 64])
+def test_one_call_fused_sketch_dims(gu, r):
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=700, r=r)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.2), one_call=True)
+
+
+def test_one_call_fused_degenerate_budgets_and_sinks(gu):
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=300)
+    n = cfg.n
+    rng = np.random.default_rng(21)
+    b = rng.choice(np.array([0, 1, 3, 4, 5, 77, n - 1, n], dtype=np.int32), size=128)
+    for s in (4, 0, 64, n + 5):
+        gu.run_and_check(cfg, b, n_sink=s, one_call=True)
+    gu.run_and_check(cfg, np.zeros(128, dtype=np.int32), one_call=True)
+
+
+def test_one_call_fused_zero_cache_and_ties(gu):
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=500)
+    K, V = wl.host_cache(cfg)
+    K[3] = 0                                         # a whole layer of zero keys: uniform scores, all tied
+    V[5, 2, 100:] = V[5, 2, 100]                     # many identical value rows
+    K[5, 2, 100:] = K[5, 2, 100]
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.3), K=K, V=V, one_call=True)
+
+
+def test_one_call_without_scores_and_fallback_paths(gu):
+    import torch
+    # few heads -> the three kernels; n above the LDS limit -> the three kernels; fp32 too
+    for cfg in (wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=900),
+                wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=2, n=40000),
+                wl.CONFIGS["c1"]):
+        gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True)
+    # scores = NULL on both paths: indices and rows must equal the run that returned scores
+    for cfg in (wl.scaled(wl.CONFIGS["c3"], layers=16, n=1000), wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=1000)):
+        K, V = wl.host_cache(cfg)
+        Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
+        b = wl.budgets_for(cfg, 0.2); off = wl.offsets_for(b); tot = int(off[-1])
+        with B.Context(cfg.layers, cfg.kv_heads, 4, 128, cfg.r, "bf16", cfg.n, cfg.sketch_seed) as ctx:
+            _, idx, Ko, Vo, _ = gu.run_path(ctx, Kd, Vd, cfg.n, b, 4, "bf16", one_call=True)
+            idx2 = torch.full((tot,), -1, dtype=torch.int32, device="cuda")
+            Ko2 = torch.zeros((tot, 128), dtype=torch.bfloat16, device="cuda"); Vo2 = torch.zeros_like(Ko2)
+            ctx.compress(Kd, Vd, cfg.n, b, 4, off, None, idx2, Ko2, Vo2)
+            torch.cuda.synchronize()
+            assert torch.equal(idx, idx2) and torch.equal(Ko.view(torch.int16), Ko2.view(torch.int16))
+            assert torch.equal(Vo.view(torch.int16), Vo2.view(torch.int16))
+
+
 def test_fold_gqa(gu):
     import torch
     L, H, g, n = 2, 3, 4, 1000
