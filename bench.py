@@ -41,6 +41,21 @@ def algorithmic_bytes(cfg, budgets, esize=2):
                 total=scores_call + select_call + compact_call)
 
 
+def measured_traffic(cfg_name, keep, fused):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE, scaled by a copy of known size), read from the
+    committed profile summary; None when no summary covers this workload."""
+    import glob
+    import re
+    kern = "fused_kernel" if fused else "curdkv_compress"
+    pat = re.compile(r"traffic_bytes_per_launch\s+%s\s+%s\s+keep=%g:\s*(\d+)" % (kern, cfg_name, keep))
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        m = pat.search(open(f).read())
+        if m:
+            return int(m.group(1))
+    return None
+
+
 def cpu_baseline(cfg, Kd, Vd, budgets, n_sink, max_seconds=25.0):
     """The CPU oracle, as it stands, on the same workload: groups in (layer, head)
     order, for as many as fit in the time budget (copies from the GPU not timed)."""
@@ -80,6 +95,9 @@ def main():
     ap.add_argument("--config", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--keep", type=float, default=None, help="keep fraction (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch) three times, so that a counter "
+                         "profile of this command holds a kernel of known traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (every (layer, head) is independent; "
@@ -143,6 +161,13 @@ def main():
 
     ab = algorithmic_bytes(cfg, budgets)
     kv_tokens = heads * n
+    if args.copy_calibration:
+        src = torch.ones((1 << 29,), dtype=torch.bfloat16, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # the three separate calls, with HIP events between them
     ms_calls, evs = timed(step_calls)
@@ -178,7 +203,7 @@ def main():
                      "kernel": "fused_kernel (whole path, one workgroup per head)" if fused else
                                "curdkv_compress (scores, select and compact kernels)",
                      "achieved": kern_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": kern_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": kern_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(cfg.name, keep, fused),
                      "algorithmic_bytes_per_launch": ab["total"], "avg_ms": kern_ms},
         "three_calls": calls,
     }
