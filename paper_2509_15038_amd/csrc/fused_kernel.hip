@@ -45,11 +45,11 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     {
         SketchRegs<CB> G;
         load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
-        const int64_t tiles = ((int64_t)n + kTileTokens - 1) / kTileTokens;
-        int64_t per_wave = (tiles + kFusedWaves - 1) / kFusedWaves;
+        const int32_t tiles = (n + kTileTokens - 1) / kTileTokens;
+        int32_t per_wave = (tiles + kFusedWaves - 1) / kFusedWaves;
         per_wave += per_wave & 1;                  // whole pairs
-        const int64_t t_begin = (int64_t)wave * per_wave;
-        const int64_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
+        const int32_t t_begin = wave * per_wave;
+        const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
         acc = scan_tiles<CB>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane);
     }
     // ---- 2. sum over the head ----------------------------------------------------------

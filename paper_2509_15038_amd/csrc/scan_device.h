@@ -86,12 +86,13 @@ __device__ __forceinline__ float combine_rows(float lk, float lv) {
 // Scores tiles [t_begin, t_end) of one head; the score of token `row` is written
 // to lds_rows[row - row0].  t_begin must be even, and t_end even or equal to
 // ceil(n/32): tiles are handled in pairs and a missing second tile is taken to
-// lie beyond n.  Returns this lane's sum of
-// the scores it wrote.  Kh, Vh: the head's rows, 16 chunks of 16 bytes each.
+// lie beyond n.  Returns this lane's sum of the scores it wrote.  Kh, Vh: the
+// head's rows, 16 chunks of 16 bytes each.  Token and tile numbers are 32-bit
+// (n < 2^31) to keep the address arithmetic out of the register budget.
 template <int CB>
 __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4* __restrict__ Kh,
-                                            const uint4* __restrict__ Vh, int64_t n, int64_t t_begin,
-                                            int64_t t_end, float* lds_rows, int64_t row0, int lane) {
+                                            const uint4* __restrict__ Vh, int32_t n, int32_t t_begin,
+                                            int32_t t_end, float* lds_rows, int32_t row0, int lane) {
     const int tok = lane & 15, q = lane >> 4;
     float acc_sum = 0.f;
     float pend = 0.f;                                           // this lane's score of the current pair
@@ -99,13 +100,14 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
     // CHECK = false is for tiles known to lie entirely below n: no clamping, no
     // predicate, hence no branch, which keeps the steady-state loop one basic
     // block so that the compiler's wait counts let loads stay in flight.
-    auto load_tile = [&](TileRegs& r, int64_t tile, auto check) {
+    auto load_tile = [&](TileRegs& r, int32_t tile, auto check) {
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-            int64_t row = tile * kTileTokens + t2 * 16 + tok;
+            int32_t row = tile * kTileTokens + t2 * 16 + tok;
             if (decltype(check)::value) row = row < n ? row : n - 1;   // ragged tail: reload the last row
-            const uint4* kp = Kh + row * 16 + q;
-            const uint4* vp = Vh + row * 16 + q;
+            const size_t off = (size_t)(uint32_t)row * 16 + q;
+            const uint4* kp = Kh + off;
+            const uint4* vp = Vh + off;
 #pragma unroll
             for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
 #pragma unroll
@@ -137,8 +139,8 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
             pend = (q == slot * 2 + t2) ? lkv : pend;
         }
     };
-    auto store_pair = [&](int64_t tile, auto check) {           // lane L holds token tile*32 + L
-        const int64_t row = tile * kTileTokens + lane;
+    auto store_pair = [&](int32_t tile, auto check) {           // lane L holds token tile*32 + L
+        const int32_t row = tile * kTileTokens + lane;
         if (!decltype(check)::value || row < n) {
             lds_rows[row - row0] = pend;
             acc_sum += pend;
@@ -149,13 +151,13 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
 
     if (t_begin < t_end) {
         TileRegs ra, rb;
-        int64_t t = t_begin;
+        int32_t t = t_begin;
         // both buffers are always filled (a lone tile is simply loaded twice): a
         // conditional load here would make every wait in the loop below pessimistic
         load_tile(ra, t, checked);
         load_tile(rb, t + 1 < t_end ? t + 1 : t, checked);
-        const int64_t full = n / kTileTokens;                   // tiles with all 32 rows below n
-        const int64_t t_steady = t_end < full ? t_end : full;
+        const int32_t full = n / kTileTokens;                   // tiles with all 32 rows below n
+        const int32_t t_steady = t_end < full ? t_end : full;
         for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 are whole
             compute_tile(ra, 0);
             __builtin_amdgcn_sched_barrier(0);

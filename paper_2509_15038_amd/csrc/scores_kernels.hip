@@ -50,22 +50,24 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     SketchRegs<CB> G;
     load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
 
-    const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
-    const int64_t waves_per_head = (int64_t)blocks_per_head * 4;
-    int64_t per_wave = (tiles + waves_per_head - 1) / waves_per_head;
+    const int32_t n32 = (int32_t)n;
+    const int32_t tiles = (n32 + kTileTokens - 1) / kTileTokens;
+    const int32_t waves_per_head = blocks_per_head * 4;
+    int32_t per_wave = (tiles + waves_per_head - 1) / waves_per_head;
     per_wave += per_wave & 1;                                   // whole pairs
-    const int64_t t_begin = ((int64_t)blk * 4 + wave) * per_wave;
-    const int64_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
+    const int32_t t_begin = (blk * 4 + wave) * per_wave;
+    const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
     const uint4* Kh = K + (size_t)head * n * 16;                // 16 chunks of 16 bytes per row
     const uint4* Vh = V + (size_t)head * n * 16;
     float* sh = scores + (size_t)head * n;
+    float* mine = stage[wave];
     float acc_sum = 0.f;
-    for (int64_t seg = t_begin; seg < t_end; seg += kStageTiles) {
-        const int64_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
-        const int64_t r0 = seg * kTileTokens;
-        acc_sum += scan_tiles<CB>(G, Kh, Vh, n, seg, seg_end, stage[wave], r0, lane);
-        const int64_t r1 = seg_end * kTileTokens < n ? seg_end * kTileTokens : n;
-        for (int64_t r = r0 + lane; r < r1; r += 64) sh[r] = stage[wave][r - r0];
+    for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
+        const int32_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
+        const int32_t r0 = seg * kTileTokens;
+        acc_sum += scan_tiles<CB>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane);
+        const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
+        for (int32_t r = r0 + lane; r < r1; r += 64) sh[r] = mine[r - r0];
     }
     block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
 }

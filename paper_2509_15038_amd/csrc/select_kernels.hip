@@ -9,29 +9,79 @@ namespace curdkv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelFixedLds = 256 * kHistRep * 4;  // histogram bytes in the streaming kernel's dynamic LDS
+// ---------------------------------------------------------------------------
+// Streaming variant for n too large for the register-resident one.  The head's
+// scores (a few hundred KB, resident in L2 / Infinity Cache after the scoring
+// kernel) are read three times:
+//   1. histogram of key bits 31..20 (4096 bins: twelve raw bits already spread a
+//      head's keys over a few hundred bins) -> bin D1 holding the cut;
+//   2. for keys in bin D1: histogram of bits 19..10, and the keys themselves are
+//      appended to an LDS list; bits 9..0 are then resolved from that list (or by
+//      one more read if the list overflowed) -> exact cut key T and the number
+//      `need` of keys equal to T still wanted;
+//   3. ordered compaction, chunk after chunk in token order, carrying the running
+//      output position, so no separate counting pass is needed.
+// Loads are issued a chunk ahead of their use.
+// ---------------------------------------------------------------------------
+constexpr int kStreamU = 8;                               // keys per thread per chunk
+constexpr int kStreamChunk = kSelThreads * kStreamU;      // 8192 tokens
+constexpr int kStreamBins = 4096;
+constexpr int kStreamList = 16384;                        // in-bin keys kept in LDS
 
-// ---------------------------------------------------------------------------
-// Streaming variant for n too large for the register-resident one: every pass
-// re-reads the head's scores from memory (they sit in L2 / Infinity Cache).
-// ---------------------------------------------------------------------------
+struct StreamShared {
+    uint32_t hist[kStreamBins];
+    uint32_t list[kStreamList];
+    uint32_t wave_tot[kSelWaves];
+    uint32_t cnt[kStreamU * kSelWaves];
+    uint32_t list_count, digit, want;
+};
+
+// Finds, scanning bins from the top, the bin where the running count reaches
+// `want`; returns it through sm.digit and the rank inside it through sm.want.
+// All threads call it; hist[] holds `bins` <= 4096 counts.  Ends with a barrier.
+__device__ __forceinline__ void find_bin_from_top(StreamShared& sm, int bins, uint32_t want) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int kPer = kStreamBins / kSelThreads;       // 4 bins per thread, descending
+    uint32_t c[kPer], tot = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int b = bins - 1 - (tid * kPer + i);
+        c[i] = b >= 0 ? sm.hist[b] : 0u;
+        tot += c[i];
+    }
+    uint32_t incl = tot;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 63) sm.wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += sm.wave_tot[w];
+    uint32_t run = before + incl - tot;                   // keys in higher bins
+    if (run < want && want <= run + tot) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (want <= run + c[i]) { sm.digit = (uint32_t)(bins - 1 - (tid * kPer + i)); sm.want = want - run; break; }
+            run += c[i];
+        }
+    }
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float* __restrict__ scores,
-                                                             int64_t n, int32_t n_sink,
-                                                             const int64_t* __restrict__ offsets,
-                                                             int32_t* __restrict__ indices) {
-    extern __shared__ uint32_t dyn[];
-    uint32_t* hist = dyn;                         // [256][kHistRep]
-    __shared__ uint32_t bin_count[256];
-    __shared__ uint32_t sh_digit, sh_want;
-    __shared__ uint32_t wave_a[kSelWaves], wave_b[kSelWaves];
-
+                                                                    int64_t n, int32_t n_sink,
+                                                                    const int64_t* __restrict__ offsets,
+                                                                    int32_t* __restrict__ indices) {
+    __shared__ StreamShared sm;
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t o0 = offsets[head];
     const int64_t k = offsets[head + 1] - o0;
     int32_t* out = indices + o0;
     const float* sc = scores + (size_t)head * n;
-    const int64_t s = n_sink;
+    const int64_t s = n_sink < n ? n_sink : n;
 
     if (k <= 0) return;
     if (k <= s) {                                  // budget inside the sink block: tokens 0..k-1
@@ -44,147 +94,136 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float*
         for (int64_t j = s + tid; j < n; j += kSelThreads) out[j] = (int32_t)j;
         return;
     }
+    const int64_t chunks = (n + kStreamChunk - 1) / kStreamChunk;
 
-    // ---- the range [kmin, kmax] of the candidates --------------------------------
-    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-    {
-        const int64_t iters = (n + kSelThreads - 1) / kSelThreads;
-        for (int64_t it = 0; it < iters; it += 8) {
-            float v[8];
+    // one chunk of keys, thread-strided; tokens outside [s, n) get key 0 and valid = false
+    auto load_chunk = [&](float (&v)[kStreamU], int64_t chunk) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t j = (it + u) * kSelThreads + tid;
-                v[u] = j < n ? sc[j] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t j = (it + u) * kSelThreads + tid;
-                if (j < n) {
-                    const uint32_t key = order_key(v[u]);
-                    if (j >= s) { kmin = key < kmin ? key : kmin; kmax = key > kmax ? key : kmax; }
-                }
-            }
+        for (int u = 0; u < kStreamU; ++u) {
+            const int64_t j = chunk * kStreamChunk + u * kSelThreads + tid;
+            v[u] = j < n ? sc[j] : 0.f;
         }
-    }
+    };
+    auto is_cand = [&](int64_t chunk, int u) -> bool {
+        const int64_t j = chunk * kStreamChunk + u * kSelThreads + tid;
+        return j >= s && j < n;
+    };
+    // runs f(key, chunk, u) over every candidate, loads one chunk ahead
+    auto for_each_key = [&](auto f) {
+        float cur[kStreamU], nxt[kStreamU];
+        load_chunk(cur, 0);
+        for (int64_t c = 0; c < chunks; ++c) {
+            if (c + 1 < chunks) load_chunk(nxt, c + 1);
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t a = __shfl_xor(kmin, off, 64), b = __shfl_xor(kmax, off, 64);
-        kmin = a < kmin ? a : kmin;
-        kmax = b > kmax ? b : kmax;
-    }
-    if (lane == 0) { wave_a[wave] = kmin; wave_b[wave] = kmax; }
+            for (int u = 0; u < kStreamU; ++u)
+                if (is_cand(c, u)) f(order_key(cur[u]), c, u);
+#pragma unroll
+            for (int u = 0; u < kStreamU; ++u) cur[u] = nxt[u];
+        }
+    };
+    auto clear_hist = [&](int bins) {
+        for (int i = tid; i < bins; i += kSelThreads) sm.hist[i] = 0;
+    };
+
+    // ---- pass 1: bits 31..20 --------------------------------------------------------
+    clear_hist(kStreamBins);
+    if (tid == 0) sm.list_count = 0;
     __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
-        kmin = wave_a[w] < kmin ? wave_a[w] : kmin;
-        kmax = wave_b[w] > kmax ? wave_b[w] : kmax;
-    }
-    auto key_at = [&](int64_t j) -> uint32_t { return order_key(sc[j]); };
+    for_each_key([&](uint32_t key, int64_t, int) { atomicAdd(&sm.hist[key >> 20], 1u); });
+    __syncthreads();
+    find_bin_from_top(sm, kStreamBins, (uint32_t)m);
+    const uint32_t d1 = sm.digit;
+    uint32_t want = sm.want;
+    __syncthreads();
 
-    // ---- radix select on x = key - kmin: T = the m-th largest among tokens [s, n) ----
-    const uint32_t range = kmax - kmin;
-    int rem = range ? 32 - __clz(range) : 0;       // bits of x not yet decided
-    uint32_t fixed = 0;                            // decided high part: x >> rem
-    uint32_t want = (uint32_t)m;
-    const int64_t span = n - s;
-    const int64_t iters = (span + kSelThreads - 1) / kSelThreads;
-    bool first = true;
-    while (rem > 0) {
-        const int w = rem < 8 ? rem : 8;
-        const int shift = rem - w;
-        const uint32_t dmask = (1u << w) - 1u;
-        for (int i = tid; i < 256 * kHistRep; i += kSelThreads) hist[i] = 0;
-        __syncthreads();
-        for (int64_t it = 0; it < iters; ++it) {
-            const int64_t j = s + it * kSelThreads + tid;
-            if (j < n) {
-                const uint32_t x = key_at(j) - kmin;
-                if (first || (x >> rem) == fixed)
-                    atomicAdd(&hist[((x >> shift) & dmask) * kHistRep + (lane & (kHistRep - 1))], 1u);
-            }
+    // ---- pass 2: bits 19..10 of the keys in bin d1; keep those keys in LDS -------------
+    clear_hist(1024);
+    __syncthreads();
+    for_each_key([&](uint32_t key, int64_t, int) {
+        if ((key >> 20) == d1) {
+            atomicAdd(&sm.hist[(key >> 10) & 1023u], 1u);
+            const uint32_t slot = atomicAdd(&sm.list_count, 1u);
+            if (slot < (uint32_t)kStreamList) sm.list[slot] = key;
+        }
+    });
+    __syncthreads();
+    find_bin_from_top(sm, 1024, want);
+    const uint32_t d2 = sm.digit;
+    want = sm.want;
+    const uint32_t in_list = sm.list_count;
+    __syncthreads();
+
+    // ---- bits 9..0 -------------------------------------------------------------------
+    const uint32_t prefix22 = (d1 << 10) | d2;
+    clear_hist(1024);
+    __syncthreads();
+    if (in_list <= (uint32_t)kStreamList) {
+        for (uint32_t i = tid; i < in_list; i += kSelThreads) {
+            const uint32_t key = sm.list[i];
+            if ((key >> 10) == prefix22) atomicAdd(&sm.hist[key & 1023u], 1u);
+        }
+    } else {
+        for_each_key([&](uint32_t key, int64_t, int) {
+            if ((key >> 10) == prefix22) atomicAdd(&sm.hist[key & 1023u], 1u);
+        });
+    }
+    __syncthreads();
+    find_bin_from_top(sm, 1024, want);
+    const uint32_t T = (prefix22 << 10) | sm.digit;
+    const uint32_t need = sm.want;                 // keys equal to T still to be kept (>= 1)
+
+    // ---- pass 3: ordered compaction, chunk by chunk ------------------------------------
+    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    uint32_t gt_base = 0, eq_base = 0;             // kept / tied candidates in earlier chunks
+    float cur[kStreamU], nxt[kStreamU];
+    load_chunk(cur, 0);
+    for (int64_t c = 0; c < chunks; ++c) {
+        if (c + 1 < chunks) load_chunk(nxt, c + 1);
+        uint64_t bg[kStreamU], be[kStreamU];
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) {
+            const uint32_t key = order_key(cur[u]);
+            const bool cd = is_cand(c, u);
+            bg[u] = __ballot(cd && key > T);
+            be[u] = __ballot(cd && key == T);
+            if (lane == 0) sm.cnt[u * kSelWaves + wave] = (uint32_t)__popcll(bg[u]) | ((uint32_t)__popcll(be[u]) << 16);
         }
         __syncthreads();
-        if (tid < 256) {
-            uint32_t c = 0;
+        if (wave == 0) {                           // exclusive scan of cnt[] in (u, wave) order
+            constexpr int kPer = kStreamU * kSelWaves / 64;
+            uint32_t v[kPer], tot = 0;
 #pragma unroll
-            for (int r = 0; r < kHistRep; ++r) c += hist[tid * kHistRep + r];
-            bin_count[tid] = c;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            // lane L looks at bins 255-4L .. 252-4L (descending); find the bin where the
-            // count from the top reaches `want`
-            uint32_t c[4], tot = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { c[i] = bin_count[255 - 4 * lane - i]; tot += c[i]; }
+            for (int i = 0; i < kPer; ++i) { v[i] = sm.cnt[lane * kPer + i]; tot += v[i]; }
             uint32_t incl = tot;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t t = __shfl_up(incl, off, 64);
                 if (lane >= off) incl += t;
             }
-            uint32_t run = incl - tot;             // keys in higher bins
-            if (run < want && want <= incl) {
+            uint32_t run = incl - tot;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (want <= run + c[i]) { sh_digit = 255 - 4 * lane - i; sh_want = want - run; break; }
-                    run += c[i];
-                }
-            }
+            for (int i = 0; i < kPer; ++i) { sm.cnt[lane * kPer + i] = run; run += v[i]; }
+            if (lane == 63) sm.wave_tot[0] = incl;  // packed totals of the chunk
         }
         __syncthreads();
-        fixed = (fixed << w) | sh_digit;
-        want = sh_want;
-        rem = shift;
-        first = false;
-        __syncthreads();                           // sh_* are rewritten next pass
-    }
-    const uint32_t T = kmin + fixed;
-    const uint32_t need = want;                    // keys equal to T still to be kept (>= 1)
-
-    // ---- ordered compaction ----------------------------------------------------
-    // wave w owns the contiguous token range [w*chunk, (w+1)*chunk)
-    int64_t chunk = (n + kSelWaves - 1) / kSelWaves;
-    chunk = (chunk + 63) & ~(int64_t)63;
-    const int64_t j0 = (int64_t)wave * chunk;
-    const int64_t j1 = j0 + chunk < n ? j0 + chunk : n;
-    uint32_t cg = 0, ce = 0;
-    for (int64_t j = j0 + lane; j < j1; j += 64) {
-        if (j >= s) {
-            const uint32_t key = key_at(j);
-            cg += key > T;
-            ce += key == T;
-        }
-    }
+        const uint32_t tot_g = sm.wave_tot[0] & 0xFFFFu, tot_e = sm.wave_tot[0] >> 16;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        cg += __shfl_xor(cg, off, 64);
-        ce += __shfl_xor(ce, off, 64);
-    }
-    __syncthreads();                               // wave_a / wave_b held the key range
-    if (lane == 0) { wave_a[wave] = cg; wave_b[wave] = ce; }
-    __syncthreads();
-    uint32_t gt_before = 0, eq_before = 0;
-    for (int w = 0; w < wave; ++w) { gt_before += wave_a[w]; eq_before += wave_b[w]; }
-
-    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    for (int64_t jb = j0; jb < j1; jb += 64) {
-        const int64_t j = jb + lane;
-        bool g = false, e = false;
-        if (j < j1 && j >= s) {
-            const uint32_t key = key_at(j);
-            g = key > T;
-            e = key == T;
+        for (int u = 0; u < kStreamU; ++u) {
+            const uint32_t base = sm.cnt[u * kSelWaves + wave];
+            const bool g = (bg[u] >> lane) & 1ull, e = (be[u] >> lane) & 1ull;
+            const uint32_t pg = gt_base + (base & 0xFFFFu) + (uint32_t)__popcll(bg[u] & lt_mask);
+            const uint32_t pe = eq_base + (base >> 16) + (uint32_t)__popcll(be[u] & lt_mask);
+            const int64_t pos = s + pg + (pe < need ? pe : need);
+            // positions stay below k by construction; the comparison keeps a write inside
+            // the group's slice even if the scores were changed under the kernel
+            if ((g || (e && pe < need)) && pos < k)
+                out[pos] = (int32_t)(c * kStreamChunk + u * kSelThreads + tid);
         }
-        const uint64_t bg = __ballot(g), be = __ballot(e);
-        const uint32_t pg = gt_before + (uint32_t)__popcll(bg & lt_mask);
-        const uint32_t pe = eq_before + (uint32_t)__popcll(be & lt_mask);
-        // positions stay below k by construction; the comparison keeps a write inside
-        // the group's slice even if the scores were changed under the kernel
-        const int64_t pos = s + pg + (pe < need ? pe : need);
-        if ((g || (e && pe < need)) && pos < k) out[pos] = (int32_t)j;
-        gt_before += (uint32_t)__popcll(bg);
-        eq_before += (uint32_t)__popcll(be);
+        gt_base += tot_g;
+        eq_base += tot_e;
+        __syncthreads();                           // cnt[] is rewritten by the next chunk
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) cur[u] = nxt[u];
     }
 }
 
@@ -259,7 +298,7 @@ hipError_t launch_select(const curdkv_ctx* ctx, const float* scores, int64_t n, 
     if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
     if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
     if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
-    select_stream_kernel<<<dim3((unsigned)ctx->heads), kSelThreads, kSelFixedLds, stream>>>(
+    select_stream_kernel<<<dim3((unsigned)ctx->heads), kSelThreads, 0, stream>>>(
         scores, n, n_sink, d_offsets, indices);
     return hipGetLastError();
 }
