@@ -234,7 +234,7 @@ int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n, const int32_t
     if (rc != CURDKV_OK) return rc;
     if (total == 0) return CURDKV_OK;
     if (!indices) return CURDKV_ERR_INVALID_ARG;
-    return launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, (hipStream_t)stream) == hipSuccess
+    return launch_select(ctx, const_cast<float*>(scores), n, n_sink, ctx->plan.d_offsets, indices, (hipStream_t)stream) == hipSuccess
                ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 
@@ -275,9 +275,12 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
         }
         scores = ctx->d_scores_ws;
     }
-    if (launch_scores(ctx, K, V, n, scores, st) != hipSuccess) return CURDKV_ERR_HIP;
+    // the selection kernel normalises on the fly (and writes the normalised scores
+    // back), which saves the separate pass over the scores
+    int bph = 0;
+    if (launch_scores(ctx, K, V, n, scores, st, /*normalise=*/false, &bph) != hipSuccess) return CURDKV_ERR_HIP;
+    if (launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st, bph) != hipSuccess) return CURDKV_ERR_HIP;
     if (total == 0) return CURDKV_OK;
-    if (launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st) != hipSuccess) return CURDKV_ERR_HIP;
     return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out, st) == hipSuccess
                ? CURDKV_OK : CURDKV_ERR_HIP;
 }

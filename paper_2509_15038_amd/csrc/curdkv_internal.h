@@ -63,12 +63,19 @@ void pack_sketch(const curdkv_config& cfg, int col_blocks, const float* G, void*
 size_t packed_elems(int col_blocks);
 
 // kernel launchers; all return hipGetLastError() after the launch
+// normalise = false leaves the un-normalised products in `scores` and the per-block
+// sums in ctx->d_partial (*blocks_per_head of them per head) for launch_select to scale.
 hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
-                         float* scores, hipStream_t stream);
+                         float* scores, hipStream_t stream, bool normalise = true,
+                         int* blocks_per_head = nullptr);
 hipError_t launch_fold(const curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores,
                        hipStream_t stream);
-hipError_t launch_select(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t n_sink,
-                         const int64_t* d_offsets, int32_t* indices, hipStream_t stream);
+// scale_blocks > 0: `scores` holds un-normalised products; the kernel divides them by
+// the head's sum (ctx->d_partial, scale_blocks partial sums per head), selects on the
+// result and writes it back, which is what "Normalize" followed by selection gives.
+hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_t n_sink,
+                         const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
+                         int scale_blocks = 0);
 hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                           const int32_t* indices, const int64_t* d_offsets, int64_t total,
                           void* K_out, void* V_out, hipStream_t stream);

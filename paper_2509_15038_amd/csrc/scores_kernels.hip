@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
 
 static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
-    int64_t want = (8LL * ctx->num_cu + ctx->heads - 1) / ctx->heads;   // ~8 blocks per CU in total
+    int64_t want = (8LL * ctx->num_cu + ctx->heads - 1) / ctx->heads;   // ~8 blocks per CU in total (measured best of 2, 8, 16)
     int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
     if (want > cap) want = cap;
     if (want > kMaxBlocksPerHead) want = kMaxBlocksPerHead;
@@ -196,8 +196,9 @@ hipError_t configure_kernels(curdkv_ctx* ctx) {
 }
 
 hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
-                         float* scores, hipStream_t stream) {
+                         float* scores, hipStream_t stream, bool normalise, int* blocks_per_head) {
     const int bph = pick_blocks_per_head(ctx, n);
+    if (blocks_per_head) *blocks_per_head = bph;
     const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
@@ -216,7 +217,7 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
         }
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || !normalise) return e;
     int64_t nb = (n + 1023) / 1024;
     if (nb > 64) nb = 64;
     normalise_kernel<<<dim3((unsigned)(nb * ctx->heads)), 256, 0, stream>>>(scores, ctx->d_partial, n, bph, (int)nb);

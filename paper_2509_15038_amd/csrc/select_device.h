@@ -35,6 +35,27 @@ __device__ __forceinline__ uint32_t order_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// "Normalize" applied on the fly: v -> v / (sum of the head), the sum being the
+// per-block partial sums added in index order in double; 1/n when the sum is 0.
+// The arithmetic is the one of the stand-alone normalisation kernel.
+struct HeadScale {
+    float inv, uniform;
+    bool zero, on;
+    __device__ __forceinline__ float operator()(float v) const {
+        return !on ? v : (zero ? uniform : v * inv);
+    }
+};
+__device__ __forceinline__ HeadScale head_scale(const float* __restrict__ partial, int blocks, int64_t n) {
+    HeadScale h;
+    h.on = blocks > 0;
+    double tot = 0.0;
+    for (int i = 0; i < blocks; ++i) tot += (double)partial[i];
+    h.zero = !(tot > 0.0);
+    h.inv = h.zero ? 0.f : (float)(1.0 / tot);
+    h.uniform = (float)(1.0 / (double)n);
+    return h;
+}
+
 template <int THREADS, int KPT>
 struct SelectShared {
     static constexpr int kWaves = THREADS / 64;

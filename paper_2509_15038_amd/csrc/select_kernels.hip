@@ -70,38 +70,58 @@ __device__ __forceinline__ void find_bin_from_top(StreamShared& sm, int bins, ui
     __syncthreads();
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float* __restrict__ scores,
+__global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __restrict__ scores,
                                                                     int64_t n, int32_t n_sink,
                                                                     const int64_t* __restrict__ offsets,
-                                                                    int32_t* __restrict__ indices) {
+                                                                    int32_t* __restrict__ indices,
+                                                                    const float* __restrict__ partial,
+                                                                    int scale_blocks) {
     __shared__ StreamShared sm;
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t o0 = offsets[head];
     const int64_t k = offsets[head + 1] - o0;
     int32_t* out = indices + o0;
-    const float* sc = scores + (size_t)head * n;
+    float* sc = scores + (size_t)head * n;
     const int64_t s = n_sink < n ? n_sink : n;
+    const HeadScale scale = head_scale(partial + (size_t)head * kMaxBlocksPerHead, scale_blocks, n);
+    auto scale_all = [&]() {                       // heads that need no selection still get normalised
+        if (scale.on)
+            for (int64_t j = tid; j < n; j += kSelThreads) sc[j] = scale(sc[j]);
+    };
 
-    if (k <= 0) return;
+    if (k <= 0) { scale_all(); return; }
     if (k <= s) {                                  // budget inside the sink block: tokens 0..k-1
         for (int64_t j = tid; j < k; j += kSelThreads) out[j] = (int32_t)j;
+        scale_all();
         return;
     }
     for (int64_t j = tid; j < s; j += kSelThreads) out[j] = (int32_t)j;
     const int64_t m = k - s;                       // picks among tokens [s, n)
     if (m >= n - s) {                              // everything is kept
         for (int64_t j = s + tid; j < n; j += kSelThreads) out[j] = (int32_t)j;
+        scale_all();
         return;
     }
     const int64_t chunks = (n + kStreamChunk - 1) / kStreamChunk;
 
-    // one chunk of keys, thread-strided; tokens outside [s, n) get key 0 and valid = false
+    // one chunk of scores, thread-strided.  With on-the-fly normalisation the first
+    // pass scales and writes back; a thread always re-reads its own tokens, so later
+    // passes see the scaled values without any fence.
+    bool scaling_pass = scale.on;
     auto load_chunk = [&](float (&v)[kStreamU], int64_t chunk) {
 #pragma unroll
         for (int u = 0; u < kStreamU; ++u) {
             const int64_t j = chunk * kStreamChunk + u * kSelThreads + tid;
             v[u] = j < n ? sc[j] : 0.f;
+        }
+        if (scaling_pass) {
+#pragma unroll
+            for (int u = 0; u < kStreamU; ++u) {
+                const int64_t j = chunk * kStreamChunk + u * kSelThreads + tid;
+                v[u] = scale(v[u]);
+                if (j < n) sc[j] = v[u];
+            }
         }
     };
     auto is_cand = [&](int64_t chunk, int u) -> bool {
@@ -130,6 +150,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float*
     if (tid == 0) sm.list_count = 0;
     __syncthreads();
     for_each_key([&](uint32_t key, int64_t, int) { atomicAdd(&sm.hist[key >> 20], 1u); });
+    scaling_pass = false;
     __syncthreads();
     find_bin_from_top(sm, kStreamBins, (uint32_t)m);
     const uint32_t d1 = sm.digit;
@@ -232,20 +253,23 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(const float*
 // indices are collected in LDS and written out coalesced.
 // ---------------------------------------------------------------------------
 template <int KPT>
-__global__ __launch_bounds__(kSelThreads) void select_reg_kernel(const float* __restrict__ scores,
+__global__ __launch_bounds__(kSelThreads) void select_reg_kernel(float* __restrict__ scores,
                                                                  int32_t n, int32_t n_sink,
                                                                  const int64_t* __restrict__ offsets,
-                                                                 int32_t* __restrict__ indices, int32_t cap) {
+                                                                 int32_t* __restrict__ indices, int32_t cap,
+                                                                 const float* __restrict__ partial,
+                                                                 int scale_blocks) {
     extern __shared__ int32_t stage[];             // [cap]
     __shared__ SelectShared<kSelThreads, KPT> sm;
     const int head = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t o0 = offsets[head];
     const int32_t k = (int32_t)(offsets[head + 1] - o0);
-    if (k <= 0) return;
+    if (k <= 0 && scale_blocks <= 0) return;
     int32_t* out = indices + o0;
-    const float* sc = scores + (size_t)head * n;
+    float* sc = scores + (size_t)head * n;
     const int32_t s = n_sink < n ? n_sink : n;
+    const HeadScale scale = head_scale(partial + (size_t)head * kMaxBlocksPerHead, scale_blocks, n);
 
     uint32_t x[KPT];
     {
@@ -256,22 +280,29 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(const float* __
             v[it] = j < n ? sc[j] : 0.f;
         }
 #pragma unroll
-        for (int it = 0; it < KPT; ++it) x[it] = order_key(v[it]);
+        for (int it = 0; it < KPT; ++it) {
+            v[it] = scale(v[it]);
+            const int32_t j = it * kSelThreads + tid;
+            if (scale.on && j < n) sc[j] = v[it];
+            x[it] = order_key(v[it]);
+        }
     }
+    if (k <= 0) return;
     select_core<kSelThreads, KPT>(x, n, s, k, sm, stage, cap, out);
     const int32_t staged = k < cap ? k : cap;
     for (int32_t p = tid; p < staged; p += kSelThreads) out[p] = stage[p];
 }
 
 template <int KPT>
-static hipError_t launch_reg(const curdkv_ctx* ctx, const float* scores, int32_t n, int32_t n_sink,
-                             const int64_t* d_offsets, int32_t* indices, hipStream_t stream) {
+static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, int32_t n_sink,
+                             const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
+                             int scale_blocks) {
     const size_t fixed = sizeof(SelectShared<kSelThreads, KPT>) + 256;
     int64_t cap = ((int64_t)ctx->lds_limit - (int64_t)fixed) / 4;
     if (cap > n) cap = n;
     if (cap < 0) cap = 0;
     select_reg_kernel<KPT><<<dim3((unsigned)ctx->heads), kSelThreads, (size_t)cap * 4, stream>>>(
-        scores, n, n_sink, d_offsets, indices, (int32_t)cap);
+        scores, n, n_sink, d_offsets, indices, (int32_t)cap, ctx->d_partial, scale_blocks);
     return hipGetLastError();
 }
 
@@ -290,16 +321,17 @@ hipError_t configure_select(curdkv_ctx* ctx) {
     return hipFuncSetAttribute((const void*)select_reg_kernel<36>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
 }
 
-hipError_t launch_select(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t n_sink,
-                         const int64_t* d_offsets, int32_t* indices, hipStream_t stream) {
+hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_t n_sink,
+                         const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
+                         int scale_blocks) {
     const int32_t n32 = (int32_t)n;
-    if (n <= 4 * kSelThreads) return launch_reg<4>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
-    if (n <= 8 * kSelThreads) return launch_reg<8>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
-    if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
-    if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
-    if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream);
+    if (n <= 4 * kSelThreads) return launch_reg<4>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
+    if (n <= 8 * kSelThreads) return launch_reg<8>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
+    if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
+    if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
+    if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
     select_stream_kernel<<<dim3((unsigned)ctx->heads), kSelThreads, 0, stream>>>(
-        scores, n, n_sink, d_offsets, indices);
+        scores, n, n_sink, d_offsets, indices, ctx->d_partial, scale_blocks);
     return hipGetLastError();
 }
 
