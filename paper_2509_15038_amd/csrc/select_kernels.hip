@@ -23,7 +23,7 @@ constexpr int kSelWaves = kSelThreads / 64;
 //      output position, so no separate counting pass is needed.
 // Loads are issued a chunk ahead of their use.
 // ---------------------------------------------------------------------------
-constexpr int kStreamU = 8;                               // keys per thread per chunk
+constexpr int kStreamU = 16;                              // keys per thread per chunk
 constexpr int kStreamChunk = kSelThreads * kStreamU;      // 8192 tokens
 constexpr int kStreamBins = 4096;
 constexpr int kStreamList = 16384;                        // in-bin keys kept in LDS
