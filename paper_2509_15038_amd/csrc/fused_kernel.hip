@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
 
     // ---- 5. gather ---------------------------------------------------------------------
     constexpr int kRowsPerIter = kFusedThreads / 16;      // 32 rows per instruction
-    constexpr int kIters = 4;
+    constexpr int kIters = 8;
     const int c = tid & 15, rsub = tid >> 4;
     const u32x4* Kr = reinterpret_cast<const u32x4*>(Kh);
     const u32x4* Vr = reinterpret_cast<const u32x4*>(Vh);
