@@ -189,14 +189,25 @@ def normalise(lkv: np.ndarray) -> np.ndarray:
     return lkv / total
 
 
-def scores(K64: np.ndarray, V64: np.ndarray, G: np.ndarray) -> np.ndarray:
-    """Normalised combined scores lt in R^n of one group.
+def scores(K64: np.ndarray, V64: np.ndarray, G, source: str = "kv",
+           projection: bool = True) -> np.ndarray:
+    """Normalised scores lt in R^n of one group.
 
     K64, V64: float64 [n, d] (exact up-casts of the stored cache).
-    G: float64 [d, r] holding the storage-rounded sketch."""
-    lk = row_norm_sq(project(K64, G))
-    lv = row_norm_sq(project(V64, G))
-    return normalise(combine(lk, lv))
+    G: float64 [d, r] holding the storage-rounded sketch (unused without projection).
+
+    The two ablations of the appendix ("Ablation Study"):
+      source = "k" / "v": leverage scores from the keys or the values alone instead
+        of their elementwise product (the "Combine scores" line is dropped);
+      projection = False: the "Sample" and "Project" lines are dropped and the row
+        norms are taken on the original matrices."""
+    if source not in ("kv", "k", "v"):
+        raise ValueError(f"unknown score source {source!r}")
+    lk = row_norm_sq(project(K64, G) if projection else np.asarray(K64, dtype=np.float64))
+    lv = row_norm_sq(project(V64, G) if projection else np.asarray(V64, dtype=np.float64))
+    if source == "kv":
+        return normalise(combine(lk, lv))
+    return normalise(lk if source == "k" else lv)
 
 
 def scores_unnormalised(K64: np.ndarray, V64: np.ndarray, G: np.ndarray):
@@ -237,18 +248,18 @@ def compact(K: np.ndarray, V: np.ndarray, S: np.ndarray):
     return K[S], V[S]
 
 
-def compress_group(K: np.ndarray, V: np.ndarray, dtype: str, G: np.ndarray,
-                   k: int, s: int):
+def compress_group(K: np.ndarray, V: np.ndarray, dtype: str, G,
+                   k: int, s: int, source: str = "kv", projection: bool = True):
     """Whole of Algorithm 1 for one group.  K, V in storage form [n, d].
     Returns (lt, S, K', V')."""
-    lt = scores(to_f64(K, dtype), to_f64(V, dtype), G)
+    lt = scores(to_f64(K, dtype), to_f64(V, dtype), G, source, projection)
     S = select(lt, k, s)
     Kc, Vc = compact(K, V, S)
     return lt, S, Kc, Vc
 
 
 def compress(K: np.ndarray, V: np.ndarray, dtype: str, seed: int, r: int,
-             budgets: np.ndarray, s: int):
+             budgets: np.ndarray, s: int, source: str = "kv", projection: bool = True):
     """Algorithm 1 over a cache [layers, kv_heads, n, d] with one budget per
     (layer, head).  Returns (scores [L,H,n] float64, list of index arrays,
     offsets [L*H+1], packed K' [sum k, d], packed V' [sum k, d])."""
@@ -262,9 +273,9 @@ def compress(K: np.ndarray, V: np.ndarray, dtype: str, seed: int, r: int,
     Vp = np.empty((int(offsets[-1]), d), dtype=V.dtype)
     for l in range(L):
         for h in range(H):
-            G = sketch(seed, l, h, H, d, r, dtype)
+            G = sketch(seed, l, h, H, d, r, dtype) if projection else None
             lt, S, Kc, Vc = compress_group(K[l, h], V[l, h], dtype, G,
-                                           int(budgets[l * H + h]), s)
+                                           int(budgets[l * H + h]), s, source, projection)
             lt_all[l, h] = lt
             idx.append(S)
             o = int(offsets[l * H + h])

@@ -187,3 +187,37 @@ def test_fold_gqa():
     a = _rng(13).random(50)
     assert np.array_equal(orc.fold_gqa(np.stack([a, a, a, a])), a)     # CurDKV: identity
     assert np.array_equal(orc.fold_gqa(np.array([[1., 2.], [3., 6.]])), [2., 4.])
+
+
+# ---- ablation variants (appendix, "Ablation Study") ------------------------------
+
+def test_single_source_scores():
+    rng = _rng(14)
+    K, V = rng.standard_normal((80, 128)), rng.standard_normal((80, 128)) * 3.0
+    G = orc.sketch(13, 0, 0, 1, 128, 32, "fp32")
+    lk, lv, lkv = orc.scores_unnormalised(K, V, G)
+    assert np.allclose(orc.scores(K, V, G, source="k"), lk / lk.sum(), rtol=1e-13)
+    assert np.allclose(orc.scores(K, V, G, source="v"), lv / lv.sum(), rtol=1e-13)
+    assert np.allclose(orc.scores(K, V, G, source="kv"), lkv / lkv.sum(), rtol=1e-13)
+    # key-only scores ignore V altogether, value-only ignore K
+    assert np.array_equal(orc.scores(K, 7 * V + 1, G, source="k"), orc.scores(K, V, G, source="k"))
+    assert np.array_equal(orc.scores(K - 2, V, G, source="v"), orc.scores(K, V, G, source="v"))
+    # the product is not either factor
+    assert not np.allclose(orc.scores(K, V, G), orc.scores(K, V, G, source="k"), rtol=1e-3)
+    with pytest.raises(ValueError):
+        orc.scores(K, V, G, source="q")
+
+
+def test_no_projection_is_raw_row_norm():
+    rng = _rng(15)
+    K, V = rng.standard_normal((60, 128)), rng.standard_normal((60, 128))
+    nk, nv = np.linalg.norm(K, axis=1) ** 2, np.linalg.norm(V, axis=1) ** 2
+    assert np.allclose(orc.scores(K, V, None, "k", projection=False), nk / nk.sum(), rtol=1e-13)
+    assert np.allclose(orc.scores(K, V, None, "v", projection=False), nv / nv.sum(), rtol=1e-13)
+    assert np.allclose(orc.scores(K, V, None, "kv", projection=False), nk * nv / np.sum(nk * nv), rtol=1e-13)
+    # same as projecting through the identity
+    assert np.allclose(orc.scores(K, V, None, projection=False), orc.scores(K, V, np.eye(128)), rtol=1e-13)
+    # and the sketched scores scatter around it with the chi-square spread sqrt(2/r) per factor
+    G = orc.sketch(14, 0, 0, 1, 128, 64, "fp32")
+    lk, _, _ = orc.scores_unnormalised(K, V, G)
+    assert abs(np.sqrt(np.mean((lk / nk - 1) ** 2)) - math.sqrt(2 / 64)) < 0.06

@@ -114,3 +114,19 @@ def test_high_norm_prefix_and_value_tail_drive_selection():
     assert len(set(range(64)) & set(S.tolist())) >= 56 and set(range(4)) <= set(S.tolist())
     vn = np.sum(orc.to_f64(V, "bf16") ** 2, axis=1)
     assert np.median(vn[S]) > 2 * np.median(vn)
+
+
+def test_compress_ablation_variants_small():
+    cfg = wl.scaled(wl.CONFIGS["c2"], layers=1, kv_heads=2, n=200)
+    K, V = wl.host_cache(cfg)
+    b = np.array([40, 40], dtype=np.int32)
+    base = orc.compress(K, V, "bf16", cfg.sketch_seed, cfg.r, b, 4)
+    for source in ("k", "v"):
+        for projection in (True, False):
+            lt, idx, off, Kp, Vp = orc.compress(K, V, "bf16", cfg.sketch_seed, cfg.r, b, 4, source, projection)
+            assert np.allclose(lt.sum(-1), 1.0) and Kp.shape == (80, 128)
+            assert not np.allclose(lt, base[0], rtol=1e-3)
+            A = orc.to_f64(K[0, 1] if source == "k" else V[0, 1], "bf16")
+            if not projection:
+                rn = np.sum(A * A, axis=1)
+                assert np.allclose(lt[0, 1], rn / rn.sum(), rtol=1e-12)
