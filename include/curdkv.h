@@ -43,6 +43,13 @@ extern "C" {
 #define CURDKV_DTYPE_F32  0
 #define CURDKV_DTYPE_BF16 1
 
+/* What the score of a token is built from.  KV is the method (Algorithm 1,
+ * "Combine scores": product of key and value scores); KEY and VALUE are the
+ * ablation of the appendix ("Ablation Study") that uses one tensor alone. */
+#define CURDKV_SCORE_KV    0
+#define CURDKV_SCORE_KEY   1
+#define CURDKV_SCORE_VALUE 2
+
 typedef struct curdkv_ctx curdkv_ctx;
 
 /* Problem statement of Algorithm 1 (inputs K, V in R^{g x n x d}, projection
@@ -55,6 +62,9 @@ typedef struct curdkv_config {
     int32_t  head_dim;     /* d; supported: 128 */
     int32_t  sketch_dim;   /* r in [1, 128]; padded internally with zero columns */
     int32_t  dtype;        /* CURDKV_DTYPE_* : storage type of K, V and of G */
+    int32_t  score_source; /* CURDKV_SCORE_* ; 0 = the method's key-value product */
+    int32_t  no_projection;/* 0 = sketch with G (the method); 1 = the ablation without the Gaussian
+                              projection: squared norms of the stored rows (bf16 only) */
     int64_t  max_tokens;   /* largest n any call will pass, >= 1 */
     uint64_t seed;         /* seed of the sketch generator */
 } curdkv_config;

@@ -29,6 +29,7 @@ EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_
 class CurdkvConfig(C.Structure):
     _fields_ = [("layers", C.c_int32), ("kv_heads", C.c_int32), ("group_size", C.c_int32),
                 ("head_dim", C.c_int32), ("sketch_dim", C.c_int32), ("dtype", C.c_int32),
+                ("score_source", C.c_int32), ("no_projection", C.c_int32),
                 ("max_tokens", C.c_int64), ("seed", C.c_uint64)]
 
 
@@ -74,9 +75,16 @@ def strerror(code: int) -> str:
     return lib().curdkv_strerror(int(code)).decode()
 
 
-def make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed):
+SCORE_KV, SCORE_KEY, SCORE_VALUE = 0, 1, 2
+_SOURCES = {"kv": SCORE_KV, "k": SCORE_KEY, "v": SCORE_VALUE}
+
+
+def make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed,
+                source="kv", projection=True):
     return CurdkvConfig(int(layers), int(kv_heads), int(group_size), int(head_dim),
                         int(sketch_dim), _DTYPES[dtype] if isinstance(dtype, str) else int(dtype),
+                        _SOURCES[source] if isinstance(source, str) else int(source),
+                        0 if projection else 1,
                         int(max_tokens), int(seed) & 0xFFFFFFFFFFFFFFFF)
 
 
@@ -113,9 +121,10 @@ class Context:
     """Owns one curdkv_ctx.  Methods mirror the C entry points and return the raw
     status code through CurdkvError on failure."""
 
-    def __init__(self, layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed):
+    def __init__(self, layers, kv_heads, group_size, head_dim, sketch_dim, dtype, max_tokens, seed,
+                 source="kv", projection=True):
         self.cfg = make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype,
-                               max_tokens, seed)
+                               max_tokens, seed, source, projection)
         self._h = C.c_void_p()
         rc = lib().curdkv_create(C.byref(self._h), C.byref(self.cfg))
         if rc != OK:

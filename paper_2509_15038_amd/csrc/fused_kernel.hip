@@ -26,7 +26,7 @@ constexpr int kFusedThreads = 512;
 constexpr int kFusedWaves = kFusedThreads / 64;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <int CB, int KPT>
+template <int CB, int KPT, int SRC, bool PROJ>
 __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     int32_t n, int32_t n_sink, const int64_t* __restrict__ offsets, float* __restrict__ scores_out,
@@ -44,13 +44,13 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     float acc;
     {
         SketchRegs<CB> G;
-        load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
+        if (PROJ) load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
         const int32_t tiles = (n + kTileTokens - 1) / kTileTokens;
         int32_t per_wave = (tiles + kFusedWaves - 1) / kFusedWaves;
         per_wave += per_wave & 1;                  // whole pairs
         const int32_t t_begin = wave * per_wave;
         const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
-        acc = scan_tiles<CB>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane);
+        acc = scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane);
     }
     // ---- 2. sum over the head ----------------------------------------------------------
     acc = wave_sum(acc);
@@ -120,37 +120,64 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     }
 }
 
-template <int CB, int KPT>
-static hipError_t launch_one(const curdkv_ctx* ctx, const void* K, const void* V, int32_t n,
-                             int32_t n_sink, const int64_t* d_offsets, float* scores,
-                             int32_t* indices, void* K_out, void* V_out, hipStream_t stream) {
-    const size_t lds = (((size_t)n + 63) & ~(size_t)63) * 4;
-    fused_kernel<CB, KPT><<<dim3((unsigned)ctx->heads), kFusedThreads, lds, stream>>>(
-        (const uint4*)K, (const uint4*)V, (const uint4*)ctx->d_G, n, n_sink, d_offsets, scores,
-        indices, (u32x4*)K_out, (u32x4*)V_out);
+struct FusedArgs {
+    const curdkv_ctx* ctx;
+    const void *K, *V;
+    int32_t n, n_sink;
+    const int64_t* d_offsets;
+    float* scores;
+    int32_t* indices;
+    void *K_out, *V_out;
+    hipStream_t stream;
+    int dyn;                 // >= 0: only raise the kernel's dynamic LDS limit to this, no launch
+};
+
+template <int CB, int KPT, int SRC, bool PROJ>
+static hipError_t one(const FusedArgs& a) {
+    if (a.dyn >= 0)
+        return hipFuncSetAttribute((const void*)fused_kernel<CB, KPT, SRC, PROJ>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, a.dyn);
+    const size_t lds = (((size_t)a.n + 63) & ~(size_t)63) * 4;
+    fused_kernel<CB, KPT, SRC, PROJ><<<dim3((unsigned)a.ctx->heads), kFusedThreads, lds, a.stream>>>(
+        (const uint4*)a.K, (const uint4*)a.V, (const uint4*)a.ctx->d_G, a.n, a.n_sink, a.d_offsets,
+        a.scores, a.indices, (u32x4*)a.K_out, (u32x4*)a.V_out);
     return hipGetLastError();
 }
 
-template <int CB, int KPT>
-static hipError_t configure_one(int dyn) {
-    return hipFuncSetAttribute((const void*)fused_kernel<CB, KPT>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
+template <int CB, int KPT, bool PROJ>
+static hipError_t by_source(const FusedArgs& a, int source) {
+    switch (source) {
+        case CURDKV_SCORE_KEY: return one<CB, KPT, kSrcK, PROJ>(a);
+        case CURDKV_SCORE_VALUE: return one<CB, KPT, kSrcV, PROJ>(a);
+        default: return one<CB, KPT, kSrcKV, PROJ>(a);
+    }
+}
+
+// picks the instantiation for (sketch width, n, score source, projection)
+static hipError_t dispatch(const FusedArgs& a, int col_blocks, bool small, int source, bool proj) {
+    if (!proj) return small ? by_source<2, 32, false>(a, source) : by_source<2, 64, false>(a, source);
+    if (col_blocks == 1) return small ? by_source<2, 32, true>(a, source) : by_source<2, 64, true>(a, source);
+    return small ? by_source<4, 32, true>(a, source) : by_source<4, 64, true>(a, source);
 }
 
 hipError_t configure_fused(curdkv_ctx* ctx) {
     const int dyn = ctx->lds_limit - 16 * 1024;
     if (dyn <= 48 * 1024) return hipSuccess;
-    hipError_t e;
-    if ((e = configure_one<2, 32>(dyn)) != hipSuccess) return e;
-    if ((e = configure_one<2, 64>(dyn)) != hipSuccess) return e;
-    if ((e = configure_one<4, 32>(dyn)) != hipSuccess) return e;
-    return configure_one<4, 64>(dyn);
+    if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return hipSuccess;
+    FusedArgs a{};
+    a.dyn = dyn;
+    for (int small = 0; small < 2; ++small) {
+        const hipError_t e = dispatch(a, ctx->col_blocks, small != 0, ctx->cfg.score_source, !ctx->cfg.no_projection);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // The fused kernel applies when a head's scores fit in LDS and there are enough
 // heads to occupy the GPU with one workgroup each.
 bool fused_applicable(const curdkv_ctx* ctx, int64_t n) {
-    if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return false;
+    if (ctx->cfg.dtype != CURDKV_DTYPE_BF16) return false;
+    if (ctx->col_blocks > 2 && !ctx->cfg.no_projection) return false;
     if (n > 64 * kFusedThreads) return false;
     const size_t lds = (((size_t)n + 63) & ~(size_t)63) * 4 + sizeof(SelectShared<kFusedThreads, 64>) + 1024;
     if (lds > (size_t)ctx->lds_limit) return false;
@@ -160,14 +187,9 @@ bool fused_applicable(const curdkv_ctx* ctx, int64_t n) {
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
                         void* V_out, hipStream_t stream) {
-    const int32_t n32 = (int32_t)n;
-    const bool small = n <= 32 * kFusedThreads;
-    if (ctx->col_blocks == 1) {
-        return small ? launch_one<2, 32>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream)
-                     : launch_one<2, 64>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream);
-    }
-    return small ? launch_one<4, 32>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream)
-                 : launch_one<4, 64>(ctx, K, V, n32, n_sink, d_offsets, scores, indices, K_out, V_out, stream);
+    FusedArgs a{ctx, K, V, (int32_t)n, n_sink, d_offsets, scores, indices, K_out, V_out, stream, -1};
+    return dispatch(a, ctx->col_blocks, n <= 32 * kFusedThreads, ctx->cfg.score_source,
+                    !ctx->cfg.no_projection);
 }
 
 }  // namespace curdkv

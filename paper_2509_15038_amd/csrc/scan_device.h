@@ -89,7 +89,26 @@ __device__ __forceinline__ float combine_rows(float lk, float lv) {
 // lie beyond n.  Returns this lane's sum of the scores it wrote.  Kh, Vh: the
 // head's rows, 16 chunks of 16 bytes each.  Token and tile numbers are 32-bit
 // (n < 2^31) to keep the address arithmetic out of the register budget.
-template <int CB>
+//
+// SRC selects the ablation of the appendix ("Ablation Study"): kSrcKV is the
+// method itself (product of key and value scores), kSrcK / kSrcV score from one
+// tensor only and never load the other.  PROJ = false drops the sketch: the score
+// is the squared norm of the stored row (the four lanes of a token hold 32 of its
+// 128 elements each), so no MFMA and no G.
+constexpr int kSrcKV = 0, kSrcK = 1, kSrcV = 2;
+
+__device__ __forceinline__ float chunk_sum_sq(const Chunk& c, float acc) {
+    const uint32_t w[4] = {c.u.x, c.u.y, c.u.z, c.u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xFFFF0000u);
+        acc = fmaf(lo, lo, acc);
+        acc = fmaf(hi, hi, acc);
+    }
+    return acc;
+}
+
+template <int CB, int SRC = kSrcKV, bool PROJ = true>
 __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4* __restrict__ Kh,
                                             const uint4* __restrict__ Vh, int32_t n, int32_t t_begin,
                                             int32_t t_end, float* lds_rows, int32_t row0, int lane) {
@@ -108,33 +127,48 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
             const size_t off = (size_t)(uint32_t)row * 16 + q;
             const uint4* kp = Kh + off;
             const uint4* vp = Vh + off;
+            if (SRC != kSrcV) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
+                for (int s = 0; s < 4; ++s) r.k[t2][s].u = kp[s * 4];
+            }
+            if (SRC != kSrcK) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) r.v[t2][s].u = vp[s * 4];
+                for (int s = 0; s < 4; ++s) r.v[t2][s].u = vp[s * 4];
+            }
         }
     };
     auto compute_tile = [&](const TileRegs& r, int slot) {      // slot: 0 = first tile of the pair
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
-            f32x4 ak[CB], av[CB];
+            // a tensor that is not scored contributes 1/4 per lane: four lanes make exactly 1
+            float lk = SRC == kSrcV ? 0.25f : 0.f, lv = SRC == kSrcK ? 0.25f : 0.f;
+            if (PROJ) {
+                f32x4 ak[CB], av[CB];
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) { ak[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; av[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+                for (int cb = 0; cb < CB; ++cb) { ak[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; av[cb] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb) {
-                    ak[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.k[t2][s].v, ak[cb], 0, 0, 0);
-                    av[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.v[t2][s].v, av[cb], 0, 0, 0);
+                    for (int cb = 0; cb < CB; ++cb) {
+                        if (SRC != kSrcV)
+                            ak[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.k[t2][s].v, ak[cb], 0, 0, 0);
+                        if (SRC != kSrcK)
+                            av[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(G.g[cb][s], r.v[t2][s].v, av[cb], 0, 0, 0);
+                    }
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (SRC != kSrcV) lk = fmaf(ak[cb][e], ak[cb][e], lk);
+                        if (SRC != kSrcK) lv = fmaf(av[cb][e], av[cb][e], lv);
+                    }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    if (SRC != kSrcV) lk = chunk_sum_sq(r.k[t2][s], lk);
+                    if (SRC != kSrcK) lv = chunk_sum_sq(r.v[t2][s], lv);
                 }
-            float lk = 0.f, lv = 0.f;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    lk = fmaf(ak[cb][e], ak[cb][e], lk);
-                    lv = fmaf(av[cb][e], av[cb][e], lv);
-                }
+            }
             const float lkv = combine_rows(lk, lv);
             pend = (q == slot * 2 + t2) ? lkv : pend;
         }

@@ -38,7 +38,7 @@ __device__ __forceinline__ void block_partial_store(float wave_total, float* dst
 // ---------------------------------------------------------------------------
 constexpr int kStageTiles = 64;     // tiles (of 32 tokens) a wave collects between bursts: 8 KB
 
-template <int CB>
+template <int CB, int SRC, bool PROJ>
 __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     SketchRegs<CB> G;
-    load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
+    if (PROJ) load_sketch<CB>(G, Gp + (size_t)head * (CB * 4 * 64), lane);
 
     const int32_t n32 = (int32_t)n;
     const int32_t tiles = (n32 + kTileTokens - 1) / kTileTokens;
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
         const int32_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
         const int32_t r0 = seg * kTileTokens;
-        acc_sum += scan_tiles<CB>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane);
+        acc_sum += scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane);
         const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
         for (int32_t r = r0 + lane; r < r1; r += 64) sh[r] = mine[r - r0];
     }
@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
 template <int CB>
 __global__ __launch_bounds__(256) void scores_f32_kernel(
     const float4* __restrict__ K, const float4* __restrict__ V, const float* __restrict__ Gp,
-    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
+    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
+    int source) {
     extern __shared__ float gs[];                      // [CB][64 steps][64 lanes]
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void scores_f32_kernel(
             tot += __shfl_xor(tot, 32, 64);
             l[which] = tot;
         }
-        const float lkv = l[0] * l[1];
+        const float lkv = source == CURDKV_SCORE_KV ? l[0] * l[1] : (source == CURDKV_SCORE_KEY ? l[0] : l[1]);
         if (half == 0 && row < n) {
             sh[row] = lkv;
             acc_sum += lkv;
@@ -202,18 +203,34 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
     const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
-        switch (ctx->col_blocks) {   // 16-column MFMA blocks = 2 per 32 padded columns
-            case 1: scores_bf16_kernel<2><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            case 2: scores_bf16_kernel<4><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            default: scores_bf16_kernel<8><<<grid, block, 0, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+        float* part = ctx->d_partial;
+#define CURDKV_LAUNCH(CBV, SRCV, PROJV) \
+    scores_bf16_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph)
+#define CURDKV_BY_SRC(CBV, PROJV)                                                   \
+    switch (ctx->cfg.score_source) {                                                \
+        case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK, PROJV); break;             \
+        case CURDKV_SCORE_VALUE: CURDKV_LAUNCH(CBV, kSrcV, PROJV); break;           \
+        default: CURDKV_LAUNCH(CBV, kSrcKV, PROJV); break;                          \
+    }
+        if (ctx->cfg.no_projection) {
+            CURDKV_BY_SRC(2, false)
+        } else {
+            switch (ctx->col_blocks) {   // 16-column MFMA blocks = 2 per 32 padded columns
+                case 1: CURDKV_BY_SRC(2, true) break;
+                case 2: CURDKV_BY_SRC(4, true) break;
+                default: CURDKV_BY_SRC(8, true) break;
+            }
         }
+#undef CURDKV_BY_SRC
+#undef CURDKV_LAUNCH
     } else {
         const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float* g = (const float*)ctx->d_G;
         const size_t lds = (size_t)ctx->col_blocks * 4096 * 4;
+        const int src = ctx->cfg.score_source;
         switch (ctx->col_blocks) {
-            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
-            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph); break;
+            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
+            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
+            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
         }
     }
     hipError_t e = hipGetLastError();

@@ -75,9 +75,10 @@ def check_selection(got: np.ndarray, lt: np.ndarray, k: int, s: int, where=""):
     return int(diff.size)
 
 
-def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where=""):
+def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="",
+               source="kv", projection=True):
     """All three comparisons for one (layer, head) given host copies."""
-    lt = orc.scores(orc.to_f64(K, cfg.dtype), orc.to_f64(V, cfg.dtype), G)
+    lt = orc.scores(orc.to_f64(K, cfg.dtype), orc.to_f64(V, cfg.dtype), G, source, projection)
     rel = check_scores(scores_g, lt, where)
     ndiff = check_selection(idx_g.astype(np.int64), lt, k, s, where)
     Kc, Vc = orc.compact(K, V, idx_g.astype(np.int64))
@@ -87,7 +88,7 @@ def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="
 
 
 def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None,
-                  one_call: bool = False):
+                  one_call: bool = False, source: str = "kv", projection: bool = True):
     """Whole path on a host cache, every head compared with the oracle."""
     s = cfg.n_sink if n_sink is None else n_sink
     if K is None:
@@ -95,7 +96,7 @@ def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=No
     L, H, n = cfg.layers, cfg.kv_heads, cfg.n
     Kd, Vd = to_device(K, cfg.dtype), to_device(V, cfg.dtype)
     worst, ndiff = 0.0, 0
-    with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
+    with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed, source, projection) as ctx:
         sc, idx, Ko, Vo, off = run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype, one_call)
         sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
         Ko_h, Vo_h = to_host(Ko, cfg.dtype), to_host(Vo, cfg.dtype)
@@ -106,7 +107,8 @@ def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=No
                 a, b = int(off[i]), int(off[i + 1])
                 rel, nd = check_head(cfg, None, K[l, h], V[l, h], G, sc_h[i], idx_h[a:b],
                                      Ko_h[a:b], Vo_h[a:b], int(budgets[i]), s,
-                                     where=f"{cfg.name} l{l} h{h} n{n}")
+                                     where=f"{cfg.name} l{l} h{h} n{n} {source} proj={projection}",
+                                     source=source, projection=projection)
                 worst = max(worst, rel)
                 ndiff += nd
     return worst, ndiff

@@ -204,6 +204,34 @@ def test_one_call_without_scores_and_fallback_paths(gu):
             assert torch.equal(Vo.view(torch.int16), Vo2.view(torch.int16))
 
 
+# ---- ablation variants (appendix, "Ablation Study"): one tensor only, no projection ----
+
+@pytest.mark.parametrize("projection", [True, False])
+@pytest.mark.parametrize("source", ["kv", "k", "v"])
+def test_ablation_variants(gu, source, projection):
+    if source == "kv" and projection:
+        pytest.skip("the method itself: covered everywhere else")
+    small = wl.scaled(wl.CONFIGS["c2"], kv_heads=3, n=1500 + 7)               # three kernels
+    gu.run_and_check(small, wl.budgets_for(small), source=source, projection=projection)
+    gu.run_and_check(small, wl.budgets_for(small), source=source, projection=projection, one_call=True)
+    fused = wl.scaled(wl.CONFIGS["c3"], layers=16, n=900 + 5)                 # fused kernel
+    gu.run_and_check(fused, wl.budgets_for(fused, 0.2), source=source, projection=projection, one_call=True)
+    if projection:
+        wide = wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=2, n=2000, dirichlet_total_frac=None)   # r = 128
+        gu.run_and_check(wide, wl.budgets_for(wide, 0.1), source=source)
+        f32 = wl.CONFIGS["c1"]
+        gu.run_and_check(f32, wl.budgets_for(f32), source=source)
+
+
+def test_ablation_config_errors(gu):
+    with pytest.raises(B.CurdkvError) as e:
+        B.Context(1, 1, 1, 128, 32, "fp32", 64, 1, "kv", False)               # no projection: bf16 only
+    assert e.value.code == B.ERR_UNSUPPORTED
+    with pytest.raises(B.CurdkvError) as e:
+        B.Context(1, 1, 1, 128, 32, "bf16", 64, 1, 5, True)
+    assert e.value.code == B.ERR_INVALID_ARG
+
+
 def test_fold_gqa(gu):
     import torch
     L, H, g, n = 2, 3, 4, 1000
