@@ -26,14 +26,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
 
 
-def algorithmic_bytes(cfg, budgets, esize=2):
+def algorithmic_bytes(cfg, budgets, esize=2, source="kv"):
     """Bytes the method has to move (per step and per part).  Per head: read K and
-    V once (2*n*d*e), write the scores (4n); select reads them (4n) and writes
-    indices (4k); compact reads indices (4k), reads and writes k rows of K and V."""
+    V once (2*n*d*e; one of them only for the key-only / value-only ablation),
+    write the scores (4n); select reads them (4n) and writes indices (4k); compact
+    reads indices (4k), reads and writes k rows of K and V."""
     heads, n, d = cfg.layers * cfg.kv_heads, cfg.n, cfg.d
     ksum = int(np.sum(budgets.astype(np.int64)))
     row = d * esize
-    scan = heads * n * (2 * row)
+    scan = heads * n * ((2 if source == "kv" else 1) * row)
     scores_call = scan + heads * n * 4
     select_call = heads * n * 4 + ksum * 4
     compact_call = ksum * (4 + 4 * row)
@@ -56,7 +57,7 @@ def measured_traffic(cfg_name, keep, fused):
     return None
 
 
-def cpu_baseline(cfg, Kd, Vd, budgets, n_sink, max_seconds=25.0):
+def cpu_baseline(cfg, Kd, Vd, budgets, n_sink, max_seconds=25.0, source="kv", projection=True):
     """The CPU oracle, as it stands, on the same workload: groups in (layer, head)
     order, for as many as fit in the time budget (copies from the GPU not timed)."""
     import torch
@@ -75,8 +76,8 @@ def cpu_baseline(cfg, Kd, Vd, budgets, n_sink, max_seconds=25.0):
         l, h = divmod(i, H)
         K, V = to_host(Kd[l, h]), to_host(Vd[l, h])
         t0 = time.perf_counter()
-        G = orc.sketch(cfg.sketch_seed, l, h, H, cfg.d, cfg.r, cfg.dtype)
-        orc.compress_group(K, V, cfg.dtype, G, int(budgets[l * H + h]), n_sink)
+        G = orc.sketch(cfg.sketch_seed, l, h, H, cfg.d, cfg.r, cfg.dtype) if projection else None
+        orc.compress_group(K, V, cfg.dtype, G, int(budgets[l * H + h]), n_sink, source, projection)
         t_used += time.perf_counter() - t0
         done += 1
         if t_used > max_seconds:
@@ -94,6 +95,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--keep", type=float, default=None, help="keep fraction (default: the config's first)")
+    ap.add_argument("--source", default="kv", choices=["kv", "k", "v"],
+                    help="ablation: score from keys and values (the method), keys only, values only")
+    ap.add_argument("--no-projection", action="store_true", help="ablation: no Gaussian projection")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch) three times, so that a counter "
@@ -122,9 +126,10 @@ def main():
     indices = torch.empty((max(total, 1),), dtype=torch.int32, device="cuda")
     Ko = torch.empty((max(total, 1), d), dtype=torch.bfloat16, device="cuda")
     Vo = torch.empty((max(total, 1), d), dtype=torch.bfloat16, device="cuda")
-    ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed)
+    ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed, args.source,
+                    not args.no_projection)
     s = cfg.n_sink
-    fused = cfg.dtype == "bf16" and cfg.r <= 64 and n <= 32768 and heads >= 128
+    fused = cfg.dtype == "bf16" and (cfg.r <= 64 or args.no_projection) and n <= 32768 and heads >= 128
 
     def step_calls(ev=None):
         if ev:
@@ -159,7 +164,7 @@ def main():
         t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / args.steps, evs
 
-    ab = algorithmic_bytes(cfg, budgets)
+    ab = algorithmic_bytes(cfg, budgets, source=args.source)
     kv_tokens = heads * n
     if args.copy_calibration:
         src = torch.ones((1 << 29,), dtype=torch.bfloat16, device="cuda")     # 1 GiB
@@ -194,7 +199,9 @@ def main():
         "config": {"workload": f"{cfg.name}: {L} layers x {H} KV heads (GQA group {cfg.group}), "
                                f"n={n}, d={d}, r={cfg.r}, keep={keep:g} (k/head mean "
                                f"{total / heads:.0f}), sinks={s}, bf16, resident in HBM; "
-                               f"step = curdkv_compress (scores + select + compact)",
+                               f"step = curdkv_compress (scores + select + compact)"
+                               + ("" if args.source == "kv" and not args.no_projection else
+                                  f"; ablation: source={args.source}, projection={not args.no_projection}"),
                    "layers": L, "kv_heads": H, "n": n, "d": d, "r": cfg.r, "keep": keep},
         "context_tokens_per_s": n / (ms_per_step * 1e-3),
         "path_GBps": ab["total"] / (ms_per_step * 1e-3) / 1e9,
@@ -203,13 +210,16 @@ def main():
                      "kernel": "fused_kernel (whole path, one workgroup per head)" if fused else
                                "curdkv_compress (scores, select and compact kernels)",
                      "achieved": kern_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": kern_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(cfg.name, keep, fused),
+                     "frac": kern_gbs / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(cfg.name, keep, fused)
+                     if args.source == "kv" and not args.no_projection else None,
                      "algorithmic_bytes_per_launch": ab["total"], "avg_ms": kern_ms},
         "three_calls": calls,
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, Kd.view(L, H, n, d), Vd.view(L, H, n, d), budgets, s)
+        out["cpu_baseline"] = cpu_baseline(cfg, Kd.view(L, H, n, d), Vd.view(L, H, n, d), budgets, s,
+                                           source=args.source, projection=not args.no_projection)
     ctx.close()
     print(json.dumps(out))
 
