@@ -242,6 +242,45 @@ def select(lt: np.ndarray, k: int, s: int) -> np.ndarray:
     return np.sort(np.concatenate([sink, top]))
 
 
+def adaptive_budgets(lt: np.ndarray, k: int, s: int, alpha: float) -> np.ndarray:
+    """AdaCurDKV's head-wise budgets for one layer (Section 3.2, "Adaptive budget
+    allocation"): the layer keeps H*k tokens in all, chosen as the top scores
+    ACROSS the heads of the layer, except that every head is guaranteed a minimum
+    fraction alpha of the group budget (the safeguard of AdaKV, alpha = 0.20 in the
+    paper).  Returns int64 [H]: tokens to keep per head, sinks included; feeding
+    them to `select` head by head gives the layer-wide selection.
+
+    lt: float64 [H, n], the normalised scores of the layer's heads.
+
+    Reading (the paper gives one sentence and points to AdaKV): the first
+    s' = min(s, n) tokens of every head are sinks, always kept and part of the
+    head's count.  Each head's own best floor(alpha*k) tokens, sinks first, are
+    safe: that is g = max(floor(alpha*k) - s', 0) non-sink tokens per head (at
+    most n - s').  The remaining R = H*(k - s') - H*g places go to the largest
+    scores among all non-sink, non-safe tokens of the layer; equal scores are
+    taken in (head, token) order.  k <= s' leaves nothing to allot: k per head."""
+    lt = np.asarray(lt, dtype=np.float64)
+    H, n = lt.shape
+    if not (0 <= k <= n) or s < 0 or not (0.0 <= alpha <= 1.0):
+        raise ValueError("need 0 <= k <= n, s >= 0, 0 <= alpha <= 1")
+    sp = min(s, n)
+    if k <= sp:
+        return np.full(H, k, dtype=np.int64)
+    g = min(max(int(np.floor(alpha * k)) - sp, 0), n - sp)
+    R = H * (k - sp) - H * g
+    cand = lt[:, sp:]
+    # rank of every non-sink token inside its head: larger score first, then lower index
+    order = np.argsort(-cand, axis=1, kind="stable")
+    rank = np.empty_like(order)
+    rows = np.arange(H)[:, None]
+    rank[rows, order] = np.arange(n - sp)[None, :]
+    open_ = rank >= g                               # not covered by the safeguard
+    head_of = np.broadcast_to(rows, cand.shape)[open_]        # (head, token) order
+    picked = np.argsort(-cand[open_], kind="stable")[:R]
+    extra = np.bincount(head_of[picked], minlength=H)
+    return (sp + g + extra).astype(np.int64)
+
+
 def compact(K: np.ndarray, V: np.ndarray, S: np.ndarray):
     """Gather line of Algorithm 1: K'_i = K_i[S_i], V'_i = V_i[S_i], rows of the
     stored (original-type) arrays, bit for bit."""
