@@ -152,6 +152,23 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                     const int32_t* budgets, int32_t n_sink, const int64_t* offsets,
                     float* scores, int32_t* indices, void* K_out, void* V_out, void* stream);
 
+/* AdaCurDKV head-wise budgets (Section 3.2, "Adaptive budget allocation"): every
+ * layer keeps kv_heads*budget tokens in all, the top normalised scores ACROSS the
+ * heads of the layer, but each head is guaranteed its own best floor(alpha*budget)
+ * tokens (the AdaKV safeguard; the paper uses alpha = 0.20).  Reading: the first
+ * s' = min(n_sink, n) tokens of a head are sinks, always kept and counted; each
+ * head is guaranteed g = max(floor(alpha*budget) - s', 0) further tokens; the
+ * remaining kv_heads*(budget - s' - g) places of a layer go to its largest
+ * scores outside the sinks and the guaranteed ones, equal scores in (head, token)
+ * order.  budget <= s' gives `budget` to every head.
+ * scores: device float [layers, kv_heads, n], normalised, non-negative.
+ * budgets_out: DEVICE int32 [layers*kv_heads], tokens to keep per head (sinks
+ * included); each layer's entries sum to kv_heads*budget.  Copy them to the host
+ * and pass them, with their prefix sums, to curdkv_select and curdkv_compact.
+ * 0 <= budget <= n, 0 <= alpha <= 1. */
+int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
+                            int32_t n_sink, double alpha, int32_t* budgets_out, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* curdkv_strerror(int code);
 

@@ -23,7 +23,7 @@ _DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
 
 EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
            "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
-           "curdkv_strerror"]
+           "curdkv_adaptive_budgets", "curdkv_strerror"]
 
 
 class CurdkvConfig(C.Structure):
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
     L.curdkv_select.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
     L.curdkv_compact.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
     L.curdkv_compress.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
+    L.curdkv_adaptive_budgets.argtypes = [vp, vp, i64, i32, i32, C.c_double, vp, vp]
     L.curdkv_strerror.argtypes = [C.c_int]
     L.curdkv_strerror.restype = C.c_char_p
     for name in EXPORTS[:-1]:
@@ -190,3 +191,10 @@ class Context:
                                    _ptr(K_out), _ptr(V_out), _stream(stream))
         if rc != OK:
             raise CurdkvError(rc, "curdkv_compress")
+
+    def adaptive_budgets(self, scores, n: int, budget: int, n_sink: int, alpha: float, budgets_out,
+                         stream=None):
+        rc = lib().curdkv_adaptive_budgets(self._h, _ptr(scores), int(n), int(budget), int(n_sink),
+                                           float(alpha), _ptr(budgets_out), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_adaptive_budgets")

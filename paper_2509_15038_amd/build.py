@@ -15,7 +15,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libcurdkv.so")
-SOURCES = ["curdkv_api.hip", "scores_kernels.hip", "select_kernels.hip", "compact_kernels.hip", "fused_kernel.hip",
+SOURCES = ["curdkv_api.hip", "scores_kernels.hip", "select_kernels.hip", "compact_kernels.hip", "fused_kernel.hip", "adaptive_kernels.hip",
            "sketch_host.cpp"]
 
 

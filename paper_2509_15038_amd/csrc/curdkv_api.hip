@@ -2,6 +2,7 @@
 // kernel launches.  No arithmetic of the method happens here except the
 // generation of the sketch (sketch_host.cpp), which is an input of the kernels.
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -183,7 +184,7 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
         }
     std::free(G);
     if (err == CURDKV_OK && (configure_kernels(ctx) != hipSuccess || configure_select(ctx) != hipSuccess ||
-                              configure_fused(ctx) != hipSuccess))
+                              configure_fused(ctx) != hipSuccess || configure_adaptive(ctx) != hipSuccess))
         err = CURDKV_ERR_HIP;
     if (err != CURDKV_OK) { release(ctx); return err; }
     *out = ctx;
@@ -286,6 +287,22 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     if (total == 0) return CURDKV_OK;
     return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out, st) == hipSuccess
                ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
+                            int32_t n_sink, double alpha, int32_t* budgets_out, void* stream) {
+    if (!ctx || !scores || !budgets_out) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0 || budget < 0 || budget > n) return CURDKV_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return CURDKV_ERR_INVALID_ARG;
+    if (ctx->cfg.kv_heads > 1024) return CURDKV_ERR_UNSUPPORTED;
+    const int64_t sp = n_sink < n ? n_sink : n;
+    int64_t g = (int64_t)std::floor(alpha * (double)budget) - sp;
+    if (g < 0) g = 0;
+    if (g > n - sp) g = n - sp;
+    const long long H = ctx->cfg.kv_heads;
+    const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
+    return launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
+                           (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 
 }  // extern "C"

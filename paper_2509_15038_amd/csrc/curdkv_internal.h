@@ -82,6 +82,9 @@ hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, i
 hipError_t configure_kernels(curdkv_ctx* ctx);
 hipError_t configure_select(curdkv_ctx* ctx);
 hipError_t configure_fused(curdkv_ctx* ctx);
+hipError_t configure_adaptive(curdkv_ctx* ctx);
+hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t k,
+                           int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream);
 bool fused_applicable(const curdkv_ctx* ctx, int64_t n);
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,

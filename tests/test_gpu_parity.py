@@ -232,6 +232,95 @@ def test_ablation_config_errors(gu):
     assert e.value.code == B.ERR_INVALID_ARG
 
 
+# ---- AdaCurDKV head-wise budgets -----------------------------------------------------
+
+def _ada_case(gu, scores, k, s, alpha):
+    """scores: float32 [L, H, n] on the host.  GPU budgets against the oracle, layer by layer."""
+    import torch
+    L, H, n = scores.shape
+    with B.Context(L, H, 4, 128, 64, "bf16", n, 1) as ctx:
+        d = torch.from_numpy(scores).cuda()
+        out = torch.full((L * H,), -1, dtype=torch.int32, device="cuda")
+        ctx.adaptive_budgets(d, n, k, s, alpha, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().reshape(L, H)
+    for l in range(L):
+        want = orc.adaptive_budgets(scores[l].astype(np.float64), k, s, alpha)
+        assert got[l].tolist() == want.tolist(), (l, k, s, alpha)
+    return got
+
+
+@pytest.mark.parametrize("H,n", [(8, 4096 + 37), (8, 300), (3, 1000), (1, 500), (16, 700), (40, 257)])
+def test_adaptive_budgets_random_scores(gu, H, n):
+    rng = np.random.default_rng([H, n])
+    sc = (rng.lognormal(0.0, 2.0, size=(3, H, n)) * rng.lognormal(0, 1, size=(3, H, 1))).astype(np.float32)
+    sc /= sc.sum(-1, keepdims=True)
+    for (k, s, alpha) in [(n // 10, 4, 0.2), (n // 2, 4, 0.2), (n // 5, 0, 0.0), (n // 5, 4, 1.0),
+                          (n, 4, 0.2), (n - 1, 4, 0.5), (3, 4, 0.2), (0, 4, 0.2), (n // 3, n + 7, 0.2)]:
+        _ada_case(gu, sc, k, s, alpha)
+
+
+def test_adaptive_budgets_ties_across_heads(gu):
+    rng = np.random.default_rng(31)
+    H, n = 8, 2000
+    sc = (rng.integers(1, 5, size=(2, H, n)) / 64.0).astype(np.float32)       # few distinct values
+    sc[1, 3] = 0.25                                                            # one head entirely tied
+    sc[1, 5, 10:] = 0.0
+    for (k, s, alpha) in [(200, 4, 0.2), (1000, 4, 0.2), (500, 0, 0.0), (1999, 4, 0.1)]:
+        _ada_case(gu, sc, k, s, alpha)
+
+
+def test_adaptive_end_to_end_c3_shape(gu):
+    # scores -> adaptive budgets -> select -> compact, the selection being the layer-wide one
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=4, n=3000 + 11)
+    K, V = wl.host_cache(cfg)
+    L, H, n = cfg.layers, cfg.kv_heads, cfg.n
+    k, s, alpha = int(0.1 * n), 4, 0.2
+    Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
+    with B.Context(L, H, 4, 128, cfg.r, "bf16", n, cfg.sketch_seed) as ctx:
+        sc = torch.empty((L * H, n), dtype=torch.float32, device="cuda")
+        ctx.scores(Kd, Vd, n, sc)
+        bd = torch.empty((L * H,), dtype=torch.int32, device="cuda")
+        ctx.adaptive_budgets(sc, n, k, s, alpha, bd)
+        torch.cuda.synchronize()
+        budgets = bd.cpu().numpy()
+        sc_h = sc.cpu().numpy()
+        # the allocation is checked on the GPU's own fp32 scores (both sides decide on the same numbers)
+        for l in range(L):
+            want = orc.adaptive_budgets(sc_h[l * H:(l + 1) * H].astype(np.float64), k, s, alpha)
+            assert budgets[l * H:(l + 1) * H].tolist() == want.tolist()
+        assert np.all(budgets.reshape(L, H).sum(1) == H * k) and budgets.min() >= int(alpha * k)
+        assert len(set(budgets.tolist())) > 1                                   # it does adapt
+        off = wl.offsets_for(budgets)
+        idx = torch.empty((int(off[-1]),), dtype=torch.int32, device="cuda")
+        Ko = torch.empty((int(off[-1]), 128), dtype=torch.bfloat16, device="cuda"); Vo = torch.empty_like(Ko)
+        ctx.select(sc, n, budgets, s, off, idx)
+        ctx.compact(Kd, Vd, n, idx, off, Ko, Vo)
+        torch.cuda.synchronize()
+        idx_h, Ko_h, Vo_h = idx.cpu().numpy(), gu.to_host(Ko, "bf16"), gu.to_host(Vo, "bf16")
+    for l in range(L):
+        for h in range(H):
+            i = l * H + h
+            G = orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, "bf16")
+            a, b = int(off[i]), int(off[i + 1])
+            gu.check_head(cfg, None, K[l, h], V[l, h], G, sc_h[i], idx_h[a:b], Ko_h[a:b], Vo_h[a:b],
+                          int(budgets[i]), s, where=f"ada l{l} h{h}")
+
+
+def test_adaptive_budgets_errors(gu):
+    import torch
+    with B.Context(1, 2, 4, 128, 64, "bf16", 64, 1) as ctx:
+        sc = torch.zeros((2, 64), dtype=torch.float32, device="cuda")
+        out = torch.zeros((2,), dtype=torch.int32, device="cuda")
+        for args in [(sc, 64, 65, 4, 0.2, out), (sc, 64, -1, 4, 0.2, out), (sc, 64, 10, 4, 1.5, out),
+                     (sc, 64, 10, -1, 0.2, out), (None, 64, 10, 4, 0.2, out), (sc, 64, 10, 4, 0.2, None),
+                     (sc, 65, 10, 4, 0.2, out)]:
+            with pytest.raises(B.CurdkvError) as e:
+                ctx.adaptive_budgets(*args)
+            assert e.value.code == B.ERR_INVALID_ARG
+
+
 def test_fold_gqa(gu):
     import torch
     L, H, g, n = 2, 3, 4, 1000
