@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--source", default="kv", choices=["kv", "k", "v"],
                     help="ablation: score from keys and values (the method), keys only, values only")
     ap.add_argument("--no-projection", action="store_true", help="ablation: no Gaussian projection")
+    ap.add_argument("--adaptive", type=float, default=None, metavar="ALPHA",
+                    help="AdaCurDKV: also time scores -> head-wise budgets (safeguard ALPHA) -> "
+                         "select -> compact and report it under 'adaptive'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch) three times, so that a counter "
@@ -217,6 +220,35 @@ def main():
         "three_calls": calls,
     }
 
+    if args.adaptive is not None:
+        kbase = int(budgets[0])
+        bd = torch.empty((heads,), dtype=torch.int32, device="cuda")
+        bh = torch.empty((heads,), dtype=torch.int32, pin_memory=True)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        parts = []
+        for it in range(args.warmup + args.steps):
+            ev[0].record()
+            ctx.scores(Kd, Vd, n, scores)
+            ev[1].record()
+            ctx.adaptive_budgets(scores, n, kbase, s, args.adaptive, bd)
+            bh.copy_(bd, non_blocking=True)
+            ev[2].record()
+            torch.cuda.current_stream().synchronize()          # budgets are needed on the host
+            ab_ = bh.numpy().copy()
+            ao = wl.offsets_for(ab_)
+            ctx.select(scores, n, ab_, s, ao, indices)
+            ev[3].record()
+            ctx.compact(Kd, Vd, n, indices, ao, Ko, Vo)
+            ev[4].record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                parts.append([ev[j].elapsed_time(ev[j + 1]) for j in range(4)])
+        pm = np.array(parts).mean(0)
+        out["adaptive"] = {"alpha": args.adaptive, "base_budget": kbase,
+                           "ms": {"scores": float(pm[0]), "budgets_incl_copy": float(pm[1]),
+                                  "select_incl_host_gap": float(pm[2]), "compact": float(pm[3]),
+                                  "total": float(pm.sum())},
+                           "budget_min_max": [int(ab_.min()), int(ab_.max())]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Kd.view(L, H, n, d), Vd.view(L, H, n, d), budgets, s,
                                            source=args.source, projection=not args.no_projection)

@@ -85,6 +85,7 @@ void release(curdkv_ctx* ctx) {
     if (ctx->d_G) (void)hipFree(ctx->d_G);
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     if (ctx->d_scores_ws) (void)hipFree(ctx->d_scores_ws);
+    if (ctx->d_adaptive_ws) (void)hipFree(ctx->d_adaptive_ws);
     if (ctx->plan.d_buf) (void)hipFree(ctx->plan.d_buf);
     if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
     if (ctx->plan.copied) (void)hipEventDestroy(ctx->plan.copied);
@@ -301,6 +302,11 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
     if (g > n - sp) g = n - sp;
     const long long H = ctx->cfg.kv_heads;
     const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
+    if (!ctx->d_adaptive_ws && hipMalloc(&ctx->d_adaptive_ws, adaptive_workspace_bytes(ctx)) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->d_adaptive_ws = nullptr;
+        return CURDKV_ERR_OOM;
+    }
     return launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }

@@ -47,6 +47,7 @@ struct curdkv_ctx {
     size_t g_elems_per_head = 0;       // packed operand elements per (layer, group)
     void* d_G = nullptr;               // packed sketches, storage type
     float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
+    void* d_adaptive_ws = nullptr;     // histograms and per-layer state of curdkv_adaptive_budgets, on first use
     float* d_scores_ws = nullptr;      // [heads, max_tokens], allocated when curdkv_compress needs it
     int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes
     int num_cu = 0;
@@ -83,6 +84,7 @@ hipError_t configure_kernels(curdkv_ctx* ctx);
 hipError_t configure_select(curdkv_ctx* ctx);
 hipError_t configure_fused(curdkv_ctx* ctx);
 hipError_t configure_adaptive(curdkv_ctx* ctx);
+size_t adaptive_workspace_bytes(const curdkv_ctx* ctx);
 hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t k,
                            int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream);
 bool fused_applicable(const curdkv_ctx* ctx, int64_t n);
