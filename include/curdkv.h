@@ -169,6 +169,26 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
 int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
                             int32_t n_sink, double alpha, int32_t* budgets_out, void* stream);
 
+/* Scoring during generation (Section 3.2: the method "can be applied during the
+ * pre-filling as well as the token generation phase").  The un-normalised scores
+ * lKV_j of a token do not depend on the other tokens, so a growing cache is scored
+ * chunk by chunk: this call scores the m new tokens of every (layer, group),
+ * writes lKV to raw[group*stride + n_old + j] and adds their sum to sums[group]
+ * (n_old == 0 starts the sums afresh).
+ * K_new, V_new: device, [layers, kv_heads, m, head_dim], the new rows only.
+ * raw: device float [layers*kv_heads, stride]; sums: device double [layers*kv_heads].
+ * 1 <= m, 0 <= n_old, n_old + m <= stride <= max_tokens. */
+int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, int64_t m,
+                         int64_t n_old, int64_t stride, float* raw, double* sums, void* stream);
+
+/* "Normalize" for the first n tokens of a cache scored with curdkv_scores_append:
+ * scores[group*n + j] = raw[group*stride + j] / sums[group] (1/n if the sum is 0),
+ * sums being those of exactly these n tokens.  The result is what curdkv_scores
+ * gives on the n-token cache (up to the order of the additions in the sum) and
+ * goes to curdkv_select / curdkv_adaptive_budgets. */
+int curdkv_normalise(curdkv_ctx* ctx, const float* raw, const double* sums, int64_t stride,
+                     int64_t n, float* scores, void* stream);
+
 /* Text for an error code; never NULL. */
 const char* curdkv_strerror(int code);
 

@@ -311,4 +311,25 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 
+int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, int64_t m,
+                         int64_t n_old, int64_t stride, float* raw, double* sums, void* stream) {
+    if (!ctx || !K_new || !V_new || !raw || !sums) return CURDKV_ERR_INVALID_ARG;
+    if (m < 1 || n_old < 0 || stride < 1 || stride > ctx->cfg.max_tokens || m > stride - n_old)
+        return CURDKV_ERR_INVALID_ARG;
+    if (((uintptr_t)K_new | (uintptr_t)V_new) & 15u) return CURDKV_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    int bph = 0;
+    if (launch_scores(ctx, K_new, V_new, m, raw, st, /*normalise=*/false, &bph, stride, n_old) != hipSuccess)
+        return CURDKV_ERR_HIP;
+    return launch_accumulate(ctx, bph, sums, n_old == 0, st) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_normalise(curdkv_ctx* ctx, const float* raw, const double* sums, int64_t stride,
+                     int64_t n, float* scores, void* stream) {
+    if (!ctx || !raw || !sums || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || stride < n || stride > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
+    return launch_normalise_sums(ctx, raw, sums, stride, n, scores, (hipStream_t)stream) == hipSuccess
+               ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
 }  // extern "C"

@@ -41,7 +41,8 @@ constexpr int kStageTiles = 64;     // tiles (of 32 tokens) a wave collects betw
 template <int CB, int SRC, bool PROJ>
 __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
-    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head) {
+    float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
+    int64_t out_stride, int64_t out_offset) {
     __shared__ float stage[4][kStageTiles * kTileTokens];
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
     const uint4* Kh = K + (size_t)head * n * 16;                // 16 chunks of 16 bytes per row
     const uint4* Vh = V + (size_t)head * n * 16;
-    float* sh = scores + (size_t)head * n;
+    float* sh = scores + (size_t)head * out_stride + out_offset;   // score of row j goes to sh[j]
     float* mine = stage[wave];
     float acc_sum = 0.f;
     for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
@@ -80,7 +81,7 @@ template <int CB>
 __global__ __launch_bounds__(256) void scores_f32_kernel(
     const float4* __restrict__ K, const float4* __restrict__ V, const float* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
-    int source) {
+    int source, int64_t out_stride, int64_t out_offset) {
     extern __shared__ float gs[];                      // [CB][64 steps][64 lanes]
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void scores_f32_kernel(
     const int64_t stride = (int64_t)blocks_per_head * 4;
     const float4* Kh = K + (size_t)head * n * 32;      // 32 float4 per row
     const float4* Vh = V + (size_t)head * n * 32;
-    float* sh = scores + (size_t)head * n;
+    float* sh = scores + (size_t)head * out_stride + out_offset;
 
     float acc_sum = 0.f;
     for (int64_t tile = (int64_t)blk * 4 + wave; tile < tiles; tile += stride) {
@@ -197,7 +198,9 @@ hipError_t configure_kernels(curdkv_ctx* ctx) {
 }
 
 hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
-                         float* scores, hipStream_t stream, bool normalise, int* blocks_per_head) {
+                         float* scores, hipStream_t stream, bool normalise, int* blocks_per_head,
+                         int64_t out_stride, int64_t out_offset) {
+    if (out_stride <= 0) out_stride = n;
     const int bph = pick_blocks_per_head(ctx, n);
     if (blocks_per_head) *blocks_per_head = bph;
     const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
@@ -205,7 +208,7 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
         const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
         float* part = ctx->d_partial;
 #define CURDKV_LAUNCH(CBV, SRCV, PROJV) \
-    scores_bf16_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph)
+    scores_bf16_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset)
 #define CURDKV_BY_SRC(CBV, PROJV)                                                   \
     switch (ctx->cfg.score_source) {                                                \
         case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK, PROJV); break;             \
@@ -228,9 +231,9 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
         const size_t lds = (size_t)ctx->col_blocks * 4096 * 4;
         const int src = ctx->cfg.score_source;
         switch (ctx->col_blocks) {
-            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
-            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
-            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src); break;
+            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
+            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
+            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
         }
     }
     hipError_t e = hipGetLastError();
@@ -238,6 +241,50 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
     int64_t nb = (n + 1023) / 1024;
     if (nb > 64) nb = 64;
     normalise_kernel<<<dim3((unsigned)(nb * ctx->heads)), 256, 0, stream>>>(scores, ctx->d_partial, n, bph, (int)nb);
+    return hipGetLastError();
+}
+
+// Decode-phase bookkeeping: running sum of a head's un-normalised scores, and the
+// normalisation by it.  Partial sums are added in index order, in double.
+__global__ void accumulate_sums_kernel(const float* __restrict__ partial, int blocks_per_head,
+                                       double* __restrict__ sums, int heads, int reset) {
+    const int head = blockIdx.x * blockDim.x + threadIdx.x;
+    if (head >= heads) return;
+    double tot = reset ? 0.0 : sums[head];
+    for (int i = 0; i < blocks_per_head; ++i) tot += (double)partial[(size_t)head * kMaxBlocksPerHead + i];
+    sums[head] = tot;
+}
+
+__global__ __launch_bounds__(256) void normalise_sums_kernel(const float* __restrict__ raw,
+                                                             const double* __restrict__ sums,
+                                                             int64_t stride, int64_t n,
+                                                             float* __restrict__ scores,
+                                                             int chunks_per_head) {
+    const int head = blockIdx.x / chunks_per_head;
+    const int chunk = blockIdx.x - head * chunks_per_head;
+    const double tot = sums[head];
+    const bool zero = !(tot > 0.0);
+    const float inv = zero ? 0.f : (float)(1.0 / tot);
+    const float uniform = (float)(1.0 / (double)n);
+    const float* src = raw + (size_t)head * stride;
+    float* dst = scores + (size_t)head * n;
+    for (int64_t j = (int64_t)chunk * blockDim.x + threadIdx.x; j < n;
+         j += (int64_t)chunks_per_head * blockDim.x)
+        dst[j] = zero ? uniform : src[j] * inv;
+}
+
+hipError_t launch_accumulate(const curdkv_ctx* ctx, int blocks_per_head, double* sums, bool reset,
+                             hipStream_t stream) {
+    accumulate_sums_kernel<<<dim3((unsigned)((ctx->heads + 255) / 256)), 256, 0, stream>>>(
+        ctx->d_partial, blocks_per_head, sums, ctx->heads, reset ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_normalise_sums(const curdkv_ctx* ctx, const float* raw, const double* sums,
+                                 int64_t stride, int64_t n, float* scores, hipStream_t stream) {
+    int64_t nb = (n + 1023) / 1024;
+    if (nb > 64) nb = 64;
+    normalise_sums_kernel<<<dim3((unsigned)(nb * ctx->heads)), 256, 0, stream>>>(raw, sums, stride, n, scores, (int)nb);
     return hipGetLastError();
 }
 

@@ -321,6 +321,56 @@ def test_adaptive_budgets_errors(gu):
             assert e.value.code == B.ERR_INVALID_ARG
 
 
+# ---- scoring during generation: chunk by chunk, then the usual selection -----------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_incremental_scoring_matches_full_cache(gu, dtype):
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c2"], layers=2, kv_heads=3, n=1500 + 9, dtype=dtype)
+    K, V = wl.host_cache(cfg)
+    L, H, n = cfg.layers, cfg.kv_heads, cfg.n
+    heads, cap = L * H, 2048
+    chunks = [700, 1, 1, 63, 300, 1, n - 1066]            # prefill, single decode steps, ragged chunks
+    assert sum(chunks) == n
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    with B.Context(L, H, 4, 128, cfg.r, dtype, cap, cfg.sketch_seed) as ctx:
+        raw = torch.full((heads, cap), float("nan"), dtype=torch.float32, device="cuda")
+        sums = torch.full((heads,), float("nan"), dtype=torch.float64, device="cuda")
+        done = 0
+        for m in chunks:
+            Kc = gu.to_device(np.ascontiguousarray(K[:, :, done:done + m]), dtype)
+            Vc = gu.to_device(np.ascontiguousarray(V[:, :, done:done + m]), dtype)
+            ctx.scores_append(Kc, Vc, m, done, cap, raw, sums)
+            done += m
+            if done in (700, 702, n):                     # compress at several points of the stream
+                sc = torch.empty((heads, done), dtype=torch.float32, device="cuda")
+                ctx.normalise(raw, sums, cap, done, sc)
+                b = np.full(heads, done // 5, dtype=np.int32); off = wl.offsets_for(b)
+                idx = torch.empty((int(off[-1]),), dtype=torch.int32, device="cuda")
+                Kd = gu.to_device(np.ascontiguousarray(K[:, :, :done]), dtype)
+                Vd = gu.to_device(np.ascontiguousarray(V[:, :, :done]), dtype)
+                Ko = torch.empty((int(off[-1]), 128), dtype=tdt, device="cuda"); Vo = torch.empty_like(Ko)
+                ctx.select(sc, done, b, 4, off, idx)
+                ctx.compact(Kd, Vd, done, idx, off, Ko, Vo)
+                torch.cuda.synchronize()
+                sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
+                Ko_h, Vo_h = gu.to_host(Ko, dtype), gu.to_host(Vo, dtype)
+                for l in range(L):
+                    for h in range(H):
+                        i = l * H + h
+                        G = orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, dtype)
+                        a, e = int(off[i]), int(off[i + 1])
+                        gu.check_head(cfg, None, K[l, h, :done], V[l, h, :done], G, sc_h[i], idx_h[a:e],
+                                      Ko_h[a:e], Vo_h[a:e], int(b[i]), 4, where=f"incremental n={done} l{l} h{h}")
+        # rows beyond the scored ones were never touched
+        assert bool(torch.isnan(raw[:, n:]).all())
+        # argument checks
+        for args in [(Kc, Vc, 0, 0, cap, raw, sums), (Kc, Vc, 5, cap - 4, cap, raw, sums),
+                     (Kc, Vc, 5, 0, cap + 1, raw, sums), (None, Vc, 5, 0, cap, raw, sums)]:
+            with pytest.raises(B.CurdkvError):
+                ctx.scores_append(*args)
+
+
 def test_fold_gqa(gu):
     import torch
     L, H, g, n = 2, 3, 4, 1000
