@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--adaptive", type=float, default=None, metavar="ALPHA",
                     help="AdaCurDKV: also time scores -> head-wise budgets (safeguard ALPHA) -> "
                          "select -> compact and report it under 'adaptive'")
+    ap.add_argument("--append", type=int, nargs="*", default=None, metavar="M",
+                    help="scoring during generation: also time curdkv_scores_append of the last M "
+                         "tokens of the cache (several M allowed) and curdkv_normalise")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch) three times, so that a counter "
@@ -249,6 +252,33 @@ def main():
                                   "select_incl_host_gap": float(pm[2]), "compact": float(pm[3]),
                                   "total": float(pm.sum())},
                            "budget_min_max": [int(ab_.min()), int(ab_.max())]}
+    if args.append:
+        raw = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+        sums = torch.zeros((heads,), dtype=torch.float64, device="cuda")
+        K4, V4 = Kd.view(L, H, n, d), Vd.view(L, H, n, d)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        res = {}
+        for m in args.append:
+            Kc, Vc = K4[:, :, n - m:].contiguous(), V4[:, :, n - m:].contiguous()
+            ts = []
+            for it in range(args.warmup + args.steps):
+                e0.record()
+                ctx.scores_append(Kc, Vc, m, n - m, n, raw, sums)
+                e1.record()
+                torch.cuda.synchronize()
+                if it >= args.warmup:
+                    ts.append(e0.elapsed_time(e1))
+            bytes_m = heads * m * ((2 if args.source == "kv" else 1) * d * 2 + 4)
+            res[str(m)] = {"ms": float(np.mean(ts)), "GBps": bytes_m / (np.mean(ts) * 1e-3) / 1e9}
+        ts = []
+        for it in range(args.warmup + args.steps):
+            e0.record()
+            ctx.normalise(raw, sums, n, n, scores)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                ts.append(e0.elapsed_time(e1))
+        out["incremental"] = {"scores_append": res, "normalise_ms": float(np.mean(ts))}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Kd.view(L, H, n, d), Vd.view(L, H, n, d), budgets, s,
                                            source=args.source, projection=not args.no_projection)
