@@ -371,6 +371,53 @@ def test_incremental_scoring_matches_full_cache(gu, dtype):
                 ctx.scores_append(*args)
 
 
+# ---- randomised shapes and adversarial score distributions --------------------------------
+
+def test_random_small_shapes_both_paths(gu):
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        L = int(rng.integers(1, 4)); H = int(rng.choice([1, 2, 3, 8])); n = int(rng.integers(1, 700))
+        r = int(rng.choice([8, 20, 32, 64, 128])); s = int(rng.choice([0, 1, 4, 9]))
+        dtype = "bf16" if case % 4 else "fp32"
+        cfg = wl.scaled(wl.CONFIGS["c2"], layers=L, kv_heads=H, n=n, r=r, dtype=dtype)
+        b = rng.integers(0, n + 1, size=L * H).astype(np.int32)
+        print(f"  case {case}: L{L} H{H} n{n} r{r} s{s} {dtype}", flush=True)
+        gu.run_and_check(cfg, b, n_sink=s, one_call=bool(case % 2))
+    for case in range(6):                                  # enough heads for the fused kernel
+        n = int(rng.integers(1, 400)); r = int(rng.choice([20, 32, 64])); s = int(rng.choice([0, 4, 50]))
+        cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=n, r=r)
+        b = rng.integers(0, n + 1, size=128).astype(np.int32)
+        print(f"  fused case {case}: n{n} r{r} s{s}", flush=True)
+        gu.run_and_check(cfg, b, n_sink=s, one_call=True)
+
+
+@pytest.mark.parametrize("n", [5000, 33000, 50000])
+def test_select_adversarial_scores(gu, n):
+    # huge dynamic range, denormals, zeros, blocks of duplicates straddling the cut: every
+    # variant of the selection kernel (registers for n <= 36864, streaming above) must agree
+    # with the oracle exactly, since the scores are given and ties go by index
+    import torch
+    rng = np.random.default_rng(n)
+    H, s = 6, 4
+    sc = np.empty((H, n), dtype=np.float32)
+    sc[0] = np.exp2(rng.uniform(-140, 120, size=n)).astype(np.float32)          # incl. denormals
+    sc[1] = 0.0; sc[1, rng.choice(n, 50, replace=False)] = 1e-30                # almost all zero
+    sc[2] = rng.choice(np.array([1e-3, 2e-3, 3e-3], dtype=np.float32), size=n)  # three values
+    sc[3] = np.float32(1.0) + rng.integers(0, 3, size=n).astype(np.float32) * np.float32(2.0 ** -23)  # last-bit ties
+    sc[4] = np.sort(rng.random(n).astype(np.float32))                            # ascending
+    sc[5] = np.sort(rng.random(n).astype(np.float32))[::-1]                      # descending
+    for budgets in ([n // 10] * H, [n - 1, 5, n // 2, n // 3, 1, n], [0, 4, 3, n // 7, n // 2, n // 2]):
+        b = np.array(budgets, dtype=np.int32); off = wl.offsets_for(b)
+        with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
+            idx = torch.full((max(int(off[-1]), 1),), -1, dtype=torch.int32, device="cuda")
+            ctx.select(torch.from_numpy(sc).cuda(), n, b, s, off, idx)
+            torch.cuda.synchronize()
+            idx = idx.cpu().numpy()
+        for h in range(H):
+            want = orc.select(sc[h].astype(np.float64), int(b[h]), s)
+            assert np.array_equal(idx[off[h]:off[h + 1]], want), (n, h, budgets)
+
+
 def test_fold_gqa(gu):
     import torch
     L, H, g, n = 2, 3, 4, 1000
