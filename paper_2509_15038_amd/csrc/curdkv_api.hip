@@ -86,6 +86,7 @@ void release(curdkv_ctx* ctx) {
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     if (ctx->d_scores_ws) (void)hipFree(ctx->d_scores_ws);
     if (ctx->d_adaptive_ws) (void)hipFree(ctx->d_adaptive_ws);
+    if (ctx->d_zero_offsets) (void)hipFree(ctx->d_zero_offsets);
     if (ctx->plan.d_buf) (void)hipFree(ctx->plan.d_buf);
     if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
     if (ctx->plan.copied) (void)hipEventDestroy(ctx->plan.copied);
@@ -162,6 +163,12 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
         release(ctx);
         return CURDKV_ERR_OOM;
     }
+    if (hipMalloc((void**)&ctx->d_zero_offsets, off_bytes) != hipSuccess ||
+        hipMemset(ctx->d_zero_offsets, 0, off_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        release(ctx);
+        return CURDKV_ERR_OOM;
+    }
     ctx->plan.d_offsets = reinterpret_cast<int64_t*>(ctx->plan.d_buf);
     ctx->plan.d_block_info = reinterpret_cast<BlockInfo*>(ctx->plan.d_buf + off_bytes);
     if (hipEventCreateWithFlags(&ctx->plan.copied, hipEventDisableTiming) != hipSuccess) {
@@ -219,6 +226,12 @@ int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, floa
     if (!ctx || !K || !V || !scores) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
     if (((uintptr_t)K | (uintptr_t)V) & 15u) return CURDKV_ERR_INVALID_ARG;
+    // Where the fused kernel applies, its first three phases (one workgroup per head, scores
+    // held in LDS, normalised there and written once) beat the scoring + normalisation pair;
+    // all-zero offsets make it stop after the scores.
+    if (fused_applicable(ctx, n))
+        return launch_fused(ctx, K, V, n, 0, ctx->d_zero_offsets, scores, nullptr, nullptr, nullptr,
+                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
     return launch_scores(ctx, K, V, n, scores, (hipStream_t)stream) == hipSuccess ? CURDKV_OK
                                                                                   : CURDKV_ERR_HIP;
 }

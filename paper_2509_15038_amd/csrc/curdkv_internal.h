@@ -47,6 +47,7 @@ struct curdkv_ctx {
     size_t g_elems_per_head = 0;       // packed operand elements per (layer, group)
     void* d_G = nullptr;               // packed sketches, storage type
     float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
+    int64_t* d_zero_offsets = nullptr; // [heads + 1] zeros: "keep nothing", for the scores-only use of the fused kernel
     void* d_adaptive_ws = nullptr;     // histograms and per-layer state of curdkv_adaptive_budgets, on first use
     float* d_scores_ws = nullptr;      // [heads, max_tokens], allocated when curdkv_compress needs it
     int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes

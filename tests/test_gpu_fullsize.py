@@ -91,6 +91,14 @@ def test_c3_full_llama_32k_all_budgets(gu):
     _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu)
 
 
+def test_c3_quarter_model_three_kernels(gu):
+    # 64 heads are too few for the one-workgroup-per-head kernel: stand-alone scoring,
+    # normalisation, selection and gather kernels at n = 32768
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=8)
+    _full(cfg, (0.10, 0.50), [(0, 0), (7, 7)], gu)
+    _full(cfg, (0.20,), [(3, 4)], gu, one_call=True)
+
+
 def test_c3_full_one_call_fused(gu):
     _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu, one_call=True)
 
