@@ -17,10 +17,11 @@
  *     neither frees nor keeps them.  "host" pointers are ordinary host memory,
  *     read before the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  The
- *     three compute calls only enqueue work on it and do not synchronise.
+ *     compute calls only enqueue work on it and do not synchronise.
  *   - The context owns the sketches, the per-block partial sums and the device
- *     copy of the offsets.  Calls on one context must not overlap in time on
- *     different streams.
+ *     copy of the offsets, all on the device that was current at curdkv_create;
+ *     that device must be current for every later call (else INVALID_ARG).
+ *     Calls on one context must not overlap in time on different streams.
  *   - K and V are row-major [layers, kv_heads, n, head_dim] in the context's
  *     storage type; token j of group (l, h) starts at element
  *     ((l*kv_heads + h)*n + j)*head_dim.  Base pointers must be 16-byte aligned.
@@ -144,8 +145,9 @@ int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
  * scores fit in one compute unit's LDS (bf16, sketch_dim <= 64, n <= 32768) and
  * there are at least half as many (layer, group) pairs as compute units, one
  * fused kernel does everything with one workgroup per pair and the scores never
- * pass through HBM between the steps; otherwise the three kernels of the
- * separate calls are launched in order.  The normalising sum is taken in a
+ * pass through HBM between the steps (when more than 40 % of all rows are kept,
+ * only its scoring phases are used and the stand-alone selection and gather
+ * kernels follow); otherwise the kernels of the separate calls are launched.  The normalising sum is taken in a
  * different order in the two cases, so scores can differ in the last bits
  * between them. */
 int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,

@@ -38,6 +38,12 @@ int check_config(const curdkv_config* cfg) {
 
 size_t storage_bytes(int dtype) { return dtype == CURDKV_DTYPE_BF16 ? 2 : 4; }
 
+// The context's buffers live on the device that was current at curdkv_create.
+bool on_own_device(const curdkv_ctx* ctx) {
+    int dev = -1;
+    return hipGetDevice(&dev) == hipSuccess && dev == ctx->device;
+}
+
 // Checks offsets (host) and makes the device copy current on `stream`.
 int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets, int64_t n,
                  hipStream_t stream, int64_t* total) {
@@ -208,6 +214,7 @@ int curdkv_destroy(curdkv_ctx* ctx) {
 
 int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float* G_host) {
     if (!ctx || !G_host) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (layer < 0 || layer >= ctx->cfg.layers || head < 0 || head >= ctx->cfg.kv_heads)
         return CURDKV_ERR_INVALID_ARG;
     const size_t count = (size_t)ctx->cfg.head_dim * ctx->cfg.sketch_dim;
@@ -224,6 +231,7 @@ int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float*
 int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, float* scores,
                   void* stream) {
     if (!ctx || !K || !V || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
     if (((uintptr_t)K | (uintptr_t)V) & 15u) return CURDKV_ERR_INVALID_ARG;
     // Where the fused kernel applies, its first three phases (one workgroup per head, scores
@@ -238,6 +246,7 @@ int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, floa
 
 int curdkv_fold(curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores, void* stream) {
     if (!ctx || !scores_q || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
     return launch_fold(ctx, scores_q, n, scores, (hipStream_t)stream) == hipSuccess ? CURDKV_OK
                                                                                     : CURDKV_ERR_HIP;
@@ -246,6 +255,7 @@ int curdkv_fold(curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores
 int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n, const int32_t* budgets,
                   int32_t n_sink, const int64_t* offsets, int32_t* indices, void* stream) {
     if (!ctx || !scores || !budgets || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0) return CURDKV_ERR_INVALID_ARG;
     int64_t total = 0;
     const int rc = sync_offsets(ctx, offsets, budgets, n, (hipStream_t)stream, &total);
@@ -259,6 +269,7 @@ int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n, const int32_t
 int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, const int32_t* indices,
                    const int64_t* offsets, void* K_out, void* V_out, void* stream) {
     if (!ctx || !K || !V || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
     if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)K_out | (uintptr_t)V_out) & 15u) return CURDKV_ERR_INVALID_ARG;
     int64_t total = 0;
@@ -274,6 +285,7 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
                     int32_t n_sink, const int64_t* offsets, float* scores, int32_t* indices,
                     void* K_out, void* V_out, void* stream) {
     if (!ctx || !K || !V || !budgets || !offsets) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0) return CURDKV_ERR_INVALID_ARG;
     if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)K_out | (uintptr_t)V_out) & 15u) return CURDKV_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -281,7 +293,12 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     const int rc = sync_offsets(ctx, offsets, budgets, n, st, &total);
     if (rc != CURDKV_OK) return rc;
     if (total > 0 && (!indices || !K_out || !V_out)) return CURDKV_ERR_INVALID_ARG;
-    if (fused_applicable(ctx, n))
+    // One kernel for everything when it applies -- unless more than ~40 % of the rows are
+    // kept: the gather then dominates and the stand-alone gather kernel (four times the
+    // threads per CU) moves rows a little faster than the fused kernel's last phase.
+    const bool fusable = fused_applicable(ctx, n);
+    const bool big_gather = total * 5 > (int64_t)ctx->heads * n * 2;
+    if (fusable && !big_gather)
         return launch_fused(ctx, K, V, n, n_sink, ctx->plan.d_offsets, scores, indices, K_out, V_out, st) == hipSuccess
                    ? CURDKV_OK : CURDKV_ERR_HIP;
     if (!scores) {
@@ -292,6 +309,13 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
             return CURDKV_ERR_OOM;
         }
         scores = ctx->d_scores_ws;
+    }
+    if (fusable) {      // scores from the fused kernel's first phases, then select and gather kernels
+        if (launch_fused(ctx, K, V, n, 0, ctx->d_zero_offsets, scores, nullptr, nullptr, nullptr, st) != hipSuccess ||
+            launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st) != hipSuccess ||
+            launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out, st) != hipSuccess)
+            return CURDKV_ERR_HIP;
+        return CURDKV_OK;
     }
     // the selection kernel normalises on the fly (and writes the normalised scores
     // back), which saves the separate pass over the scores
@@ -306,6 +330,7 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
 int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
                             int32_t n_sink, double alpha, int32_t* budgets_out, void* stream) {
     if (!ctx || !scores || !budgets_out) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0 || budget < 0 || budget > n) return CURDKV_ERR_INVALID_ARG;
     if (!(alpha >= 0.0 && alpha <= 1.0)) return CURDKV_ERR_INVALID_ARG;
     if (ctx->cfg.kv_heads > 1024) return CURDKV_ERR_UNSUPPORTED;
@@ -327,6 +352,7 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
 int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, int64_t m,
                          int64_t n_old, int64_t stride, float* raw, double* sums, void* stream) {
     if (!ctx || !K_new || !V_new || !raw || !sums) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (m < 1 || n_old < 0 || stride < 1 || stride > ctx->cfg.max_tokens || m > stride - n_old)
         return CURDKV_ERR_INVALID_ARG;
     if (((uintptr_t)K_new | (uintptr_t)V_new) & 15u) return CURDKV_ERR_INVALID_ARG;
@@ -340,6 +366,7 @@ int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, 
 int curdkv_normalise(curdkv_ctx* ctx, const float* raw, const double* sums, int64_t stride,
                      int64_t n, float* scores, void* stream) {
     if (!ctx || !raw || !sums || !scores) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
     if (n < 1 || stride < n || stride > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
     return launch_normalise_sums(ctx, raw, sums, stride, n, scores, (hipStream_t)stream) == hipSuccess
                ? CURDKV_OK : CURDKV_ERR_HIP;
