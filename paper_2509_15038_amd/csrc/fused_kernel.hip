@@ -161,7 +161,7 @@ static hipError_t dispatch(const FusedArgs& a, int col_blocks, bool small, int s
 }
 
 hipError_t configure_fused(curdkv_ctx* ctx) {
-    const int dyn = ctx->lds_limit - 16 * 1024;
+    const int dyn = ctx->lds_limit - 24 * 1024;      // what the kernels' static LDS leaves
     if (dyn <= 48 * 1024) return hipSuccess;
     if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return hipSuccess;
     FusedArgs a{};

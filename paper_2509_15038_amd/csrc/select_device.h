@@ -17,10 +17,12 @@
 // or three bins and serialise the LDS atomics; relative to the head's own range
 // the first digit already spreads the keys over up to 256 bins.
 //
-// The selected indices are collected in an LDS staging array (positions come
-// from an exclusive scan of per-(row, wave) counts, a row being THREADS
-// consecutive tokens), so that the caller can write them out, or gather by them,
-// with coalesced accesses.
+// The compaction works on bitmaps: one ballot per row of THREADS tokens gives a
+// 64-token word of "above T" and of "equal to T" flags; one wave trims the tied
+// flags to the first `need`, scans the popcounts into output positions, and then
+// each word's set bits are listed.  The indices are collected in an LDS staging
+// array so that the caller can write them out, or gather by them, with coalesced
+// accesses.
 #pragma once
 
 #include "curdkv_internal.h"
@@ -61,7 +63,9 @@ struct SelectShared {
     static constexpr int kWaves = THREADS / 64;
     uint32_t hist[256 * kHistRep];
     uint32_t bin_count[256];
-    uint32_t cnt[KPT * kWaves];                   // low 16 bits: keys above T, high 16: keys equal to T
+    unsigned long long gmask[KPT * kWaves];       // bitmaps over the tokens, one 64-token word per (row, wave)
+    unsigned long long emask[KPT * kWaves];
+    uint32_t wpos[KPT * kWaves];                  // output position of a word's first kept token
     uint32_t wave_a[kWaves], wave_b[kWaves];
     uint32_t digit, want;
 };
@@ -174,50 +178,76 @@ __device__ __forceinline__ void select_core(uint32_t (&x)[KPT], int32_t n, int32
     const uint32_t T = fixed;                      // in x space
     const uint32_t need = want;                    // keys equal to T still to be kept (>= 1)
 
-    // ---- ordered compaction: token order is (row it, wave, lane) ----------------------
-    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    // ---- ordered compaction through bitmaps ----------------------------------------------
+    // Word w = it*kWaves + wave of a bitmap covers tokens 64w .. 64w+63, so one ballot per
+    // row is one word.  gmask marks candidates above T, emask candidates equal to T.
+    constexpr int kWords = KPT * kWaves;
     const uint32_t above = kNotCand - 1u - T;      // T < x < all-ones  <=>  x - T - 1 < above
 #pragma unroll
     for (int it = 0; it < KPT; ++it) {
         const uint64_t bg = __ballot(x[it] - T - 1u < above), be = __ballot(x[it] == T);
-        if (lane == 0) sm.cnt[it * kWaves + wave] = (uint32_t)__popcll(bg) | ((uint32_t)__popcll(be) << 16);
+        if (lane == 0) { sm.gmask[it * kWaves + wave] = bg; sm.emask[it * kWaves + wave] = be; }
     }
     __syncthreads();
-    if (wave == 0) {                               // exclusive scan of cnt[] in index order
-        constexpr int kPer = (KPT * kWaves + 63) / 64;
-        uint32_t v[kPer], tot = 0;
+    if (wave == 0) {
+        // lane L owns words L*kPer .. L*kPer+kPer-1.  First scan: tied keys before each word,
+        // to cut emask down to the first `need` of them; second scan: output position of
+        // each word's first kept token.
+        constexpr int kPer = (kWords + 63) / 64;
+        uint64_t keep[kPer];
+        uint32_t ne = 0;
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int e = lane * kPer + i;
-            v[i] = e < KPT * kWaves ? sm.cnt[e] : 0u;
-            tot += v[i];
+            const int w = lane * kPer + i;
+            keep[i] = w < kWords ? sm.emask[w] : 0ull;
+            ne += (uint32_t)__popcll(keep[i]);
         }
-        uint32_t incl = tot;
+        uint32_t incl = ne;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t t = __shfl_up(incl, off, 64);
             if (lane >= off) incl += t;
         }
-        uint32_t run = incl - tot;
+        uint32_t eq_before = incl - ne, nk = 0;
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            const int e = lane * kPer + i;
-            if (e < KPT * kWaves) sm.cnt[e] = run;
-            run += v[i];
+            const int w = lane * kPer + i;
+            uint64_t e = keep[i];
+            const uint32_t c = (uint32_t)__popcll(e);
+            if (eq_before >= need) e = 0ull;                       // quota already used up
+            else if (eq_before + c > need)                         // the word where it runs out
+                for (uint32_t drop = eq_before + c - need; drop; --drop) e &= ~(1ull << (63 - __clzll((long long)e)));
+            eq_before += c;
+            keep[i] = (w < kWords ? sm.gmask[w] : 0ull) | e;
+            nk += (uint32_t)__popcll(keep[i]);
+        }
+        incl = nk;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        uint32_t pos = (uint32_t)s + incl - nk;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            const int w = lane * kPer + i;
+            if (w < kWords) { sm.gmask[w] = keep[i]; sm.wpos[w] = pos; }
+            pos += (uint32_t)__popcll(keep[i]);
         }
     }
     __syncthreads();
-#pragma unroll
-    for (int it = 0; it < KPT; ++it) {
-        const uint32_t base = sm.cnt[it * kWaves + wave];
-        const bool g = x[it] - T - 1u < above, e = x[it] == T;
-        const uint64_t bg = __ballot(g), be = __ballot(e);
-        const uint32_t pg = (base & 0xFFFFu) + (uint32_t)__popcll(bg & lt_mask);
-        const uint32_t pe = (base >> 16) + (uint32_t)__popcll(be & lt_mask);
-        // positions stay below k by construction; the comparison keeps a write inside
-        // the group's slice whatever the keys were
-        const uint32_t pos = (uint32_t)s + pg + (pe < need ? pe : need);
-        if ((g || (e && pe < need)) && pos < (uint32_t)k) put(pos, it * THREADS + tid);
+    // one thread per word writes out that word's tokens, ascending
+    for (int w = tid; w < kWords; w += THREADS) {
+        uint64_t m = sm.gmask[w];
+        uint32_t pos = sm.wpos[w];
+        while (m) {
+            const int bit = __ffsll((unsigned long long)m) - 1;
+            m &= m - 1;
+            // positions stay below k by construction; the comparison keeps a write inside
+            // the group's slice whatever the keys were
+            if (pos < (uint32_t)k) put(pos, w * 64 + bit);
+            ++pos;
+        }
     }
     __syncthreads();
 }

@@ -307,7 +307,7 @@ static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, in
 }
 
 hipError_t configure_select(curdkv_ctx* ctx) {
-    const int dyn = ctx->lds_limit - 16 * 1024;
+    const int dyn = ctx->lds_limit - 24 * 1024;      // what the kernels' static LDS leaves
     if (dyn <= 48 * 1024) return hipSuccess;
     hipError_t e;
     e = hipFuncSetAttribute((const void*)select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
