@@ -19,20 +19,24 @@ constexpr int kSelWaves = kSelThreads / 64;
 //      appended to an LDS list; bits 9..0 are then resolved from that list (or by
 //      one more read if the list overflowed) -> exact cut key T and the number
 //      `need` of keys equal to T still wanted;
-//   3. ordered compaction, chunk after chunk in token order, carrying the running
-//      output position, so no separate counting pass is needed.
+//   3. ordered compaction through LDS bitmaps, 131072 tokens at a time, carrying the
+//      running output position, so no separate counting pass is needed.
 // Loads are issued a chunk ahead of their use.
 // ---------------------------------------------------------------------------
 constexpr int kStreamU = 16;                              // keys per thread per chunk
 constexpr int kStreamChunk = kSelThreads * kStreamU;      // 8192 tokens
 constexpr int kStreamBins = 4096;
 constexpr int kStreamList = 16384;                        // in-bin keys kept in LDS
+constexpr int kStreamSuper = 8 * kStreamChunk;            // tokens per compaction super-chunk (131072)
+constexpr int kStreamWords = kStreamSuper / 64;           // bitmap words per super-chunk
 
 struct StreamShared {
     uint32_t hist[kStreamBins];
     uint32_t list[kStreamList];
+    unsigned long long gmask[kStreamWords], emask[kStreamWords];   // "above T" / "equal to T" flags
+    uint32_t wpos[kStreamWords];                  // output position of a word's first kept token
     uint32_t wave_tot[kSelWaves];
-    uint32_t cnt[kStreamU * kSelWaves];
+    uint32_t carry[2];
     uint32_t list_count, digit, want;
 };
 
@@ -193,58 +197,92 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
     const uint32_t T = (prefix22 << 10) | sm.digit;
     const uint32_t need = sm.want;                 // keys equal to T still to be kept (>= 1)
 
-    // ---- pass 3: ordered compaction, chunk by chunk ------------------------------------
-    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    uint32_t gt_base = 0, eq_base = 0;             // kept / tied candidates in earlier chunks
-    float cur[kStreamU], nxt[kStreamU];
-    load_chunk(cur, 0);
-    for (int64_t c = 0; c < chunks; ++c) {
-        if (c + 1 < chunks) load_chunk(nxt, c + 1);
-        uint64_t bg[kStreamU], be[kStreamU];
+    // ---- pass 3: ordered compaction through bitmaps, a super-chunk of tokens at a time -------
+    // Word w of a bitmap covers tokens 64w .. 64w+63 of the super-chunk; one ballot of a wave
+    // over 64 consecutive tokens is one word.  Per super-chunk: fill the bitmaps, one wave
+    // trims the tied flags to what is still needed and scans popcounts into output positions
+    // (carrying both across super-chunks), then every word lists its set bits.
+    uint32_t eq_carry = 0, pos_carry = (uint32_t)s;
+    const int64_t chunks_per_super = kStreamSuper / kStreamChunk;
+    for (int64_t c0 = 0; c0 < chunks; c0 += chunks_per_super) {
+        const int64_t c1 = c0 + chunks_per_super < chunks ? c0 + chunks_per_super : chunks;
+        const int64_t super_base = c0 * kStreamChunk;
+        float cur[kStreamU], nxt[kStreamU];
+        load_chunk(cur, c0);
+        for (int64_t c = c0; c < c1; ++c) {
+            if (c + 1 < c1) load_chunk(nxt, c + 1);
 #pragma unroll
-        for (int u = 0; u < kStreamU; ++u) {
-            const uint32_t key = order_key(cur[u]);
-            const bool cd = is_cand(c, u);
-            bg[u] = __ballot(cd && key > T);
-            be[u] = __ballot(cd && key == T);
-            if (lane == 0) sm.cnt[u * kSelWaves + wave] = (uint32_t)__popcll(bg[u]) | ((uint32_t)__popcll(be[u]) << 16);
+            for (int u = 0; u < kStreamU; ++u) {
+                const uint32_t key = order_key(cur[u]);
+                const bool cd = is_cand(c, u);
+                const uint64_t bg = __ballot(cd && key > T), be = __ballot(cd && key == T);
+                const int w = (int)((c * kStreamChunk - super_base) / 64) + u * kSelWaves + wave;
+                if (lane == 0) { sm.gmask[w] = bg; sm.emask[w] = be; }
+            }
+#pragma unroll
+            for (int u = 0; u < kStreamU; ++u) cur[u] = nxt[u];
         }
+        const int words = (int)((c1 - c0) * (kStreamChunk / 64));
         __syncthreads();
-        if (wave == 0) {                           // exclusive scan of cnt[] in (u, wave) order
-            constexpr int kPer = kStreamU * kSelWaves / 64;
-            uint32_t v[kPer], tot = 0;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) { v[i] = sm.cnt[lane * kPer + i]; tot += v[i]; }
-            uint32_t incl = tot;
+        if (wave == 0) {
+            constexpr int kPer = kStreamWords / 64;
+            uint32_t ne = 0;
+            for (int i = 0; i < kPer; ++i) {
+                const int w = lane * kPer + i;
+                ne += w < words ? (uint32_t)__popcll(sm.emask[w]) : 0u;
+            }
+            uint32_t incl = ne;
 #pragma unroll
             for (int off = 1; off < 64; off <<= 1) {
                 const uint32_t t = __shfl_up(incl, off, 64);
                 if (lane >= off) incl += t;
             }
-            uint32_t run = incl - tot;
+            uint32_t eq_before = eq_carry + incl - ne, nk = 0;
+            const uint32_t eq_total = __shfl(incl, 63, 64);
+            for (int i = 0; i < kPer; ++i) {
+                const int w = lane * kPer + i;
+                if (w >= words) break;
+                uint64_t e = sm.emask[w];
+                const uint32_t cnt = (uint32_t)__popcll(e);
+                if (eq_before >= need) e = 0ull;                   // quota already used up
+                else if (eq_before + cnt > need)                   // the word where it runs out
+                    for (uint32_t drop = eq_before + cnt - need; drop; --drop) e &= ~(1ull << (63 - __clzll((long long)e)));
+                eq_before += cnt;
+                const uint64_t keep = sm.gmask[w] | e;
+                sm.gmask[w] = keep;
+                nk += (uint32_t)__popcll(keep);
+            }
+            incl = nk;
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) { sm.cnt[lane * kPer + i] = run; run += v[i]; }
-            if (lane == 63) sm.wave_tot[0] = incl;  // packed totals of the chunk
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_up(incl, off, 64);
+                if (lane >= off) incl += t;
+            }
+            uint32_t pos = pos_carry + incl - nk;
+            for (int i = 0; i < kPer; ++i) {
+                const int w = lane * kPer + i;
+                if (w >= words) break;
+                sm.wpos[w] = pos;
+                pos += (uint32_t)__popcll(sm.gmask[w]);
+            }
+            if (lane == 63) { sm.carry[0] = eq_carry + eq_total; sm.carry[1] = pos_carry + incl; }
         }
         __syncthreads();
-        const uint32_t tot_g = sm.wave_tot[0] & 0xFFFFu, tot_e = sm.wave_tot[0] >> 16;
-#pragma unroll
-        for (int u = 0; u < kStreamU; ++u) {
-            const uint32_t base = sm.cnt[u * kSelWaves + wave];
-            const bool g = (bg[u] >> lane) & 1ull, e = (be[u] >> lane) & 1ull;
-            const uint32_t pg = gt_base + (base & 0xFFFFu) + (uint32_t)__popcll(bg[u] & lt_mask);
-            const uint32_t pe = eq_base + (base >> 16) + (uint32_t)__popcll(be[u] & lt_mask);
-            const int64_t pos = s + pg + (pe < need ? pe : need);
-            // positions stay below k by construction; the comparison keeps a write inside
-            // the group's slice even if the scores were changed under the kernel
-            if ((g || (e && pe < need)) && pos < k)
-                out[pos] = (int32_t)(c * kStreamChunk + u * kSelThreads + tid);
+        eq_carry = sm.carry[0];
+        pos_carry = sm.carry[1];
+        for (int w = tid; w < words; w += kSelThreads) {
+            uint64_t m = sm.gmask[w];
+            uint32_t pos = sm.wpos[w];
+            while (m) {
+                const int bit = __ffsll((unsigned long long)m) - 1;
+                m &= m - 1;
+                // positions stay below k by construction; the comparison keeps a write inside
+                // the group's slice even if the scores were changed under the kernel
+                if ((int64_t)pos < k) out[pos] = (int32_t)(super_base + (int64_t)w * 64 + bit);
+                ++pos;
+            }
         }
-        gt_base += tot_g;
-        eq_base += tot_e;
-        __syncthreads();                           // cnt[] is rewritten by the next chunk
-#pragma unroll
-        for (int u = 0; u < kStreamU; ++u) cur[u] = nxt[u];
+        __syncthreads();                           // the bitmaps are refilled by the next super-chunk
     }
 }
 

@@ -126,12 +126,15 @@ def test_select_ties_lowest_index_first(gu):
         assert np.array_equal(idx[off[h]:off[h + 1]], want), h
 
 
-def test_select_large_n_streaming_ties(gu):
+@pytest.mark.parametrize("n", [70001, 131072, 300007])
+def test_select_large_n_streaming_ties(gu, n):
+    # the largest n spans three of the streaming kernel's compaction blocks, with tied keys
+    # on both sides of each boundary
     import torch
-    n, H, s = 70001, 2, 4
+    H, s = 2, 4
     rng = np.random.default_rng(12)
     sc = (rng.integers(0, 50, size=(H, n)).astype(np.float32)) * np.float32(1e-6)
-    budgets = np.array([7000, 35000], dtype=np.int32)
+    budgets = np.array([n // 10, n // 2], dtype=np.int32)
     off = wl.offsets_for(budgets)
     with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
         scd = torch.from_numpy(sc).cuda()
