@@ -58,7 +58,12 @@ int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets
     Plan& pl = ctx->plan;
     const size_t off_bytes = ((size_t)(heads + 1) * sizeof(int64_t) + 15) & ~(size_t)15;
     const size_t cmp_bytes = (size_t)(heads + 1) * sizeof(int64_t);
-    if (pl.valid && std::memcmp(pl.cached.data(), offsets, cmp_bytes) == 0) return CURDKV_OK;
+    if (pl.valid && std::memcmp(pl.cached.data(), offsets, cmp_bytes) == 0) {
+        // same offsets as last time; a caller that moved to another stream must still see the copy
+        if (pl.copy_pending && stream != pl.copy_stream &&
+            hipStreamWaitEvent(stream, pl.copied, 0) != hipSuccess) return CURDKV_ERR_HIP;
+        return CURDKV_OK;
+    }
     if (pl.copy_pending) {                       // staging buffer may still be being read
         if (hipEventSynchronize(pl.copied) != hipSuccess) return CURDKV_ERR_HIP;
         pl.copy_pending = false;
@@ -81,6 +86,7 @@ int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets
         return CURDKV_ERR_HIP;
     if (hipEventRecord(pl.copied, stream) != hipSuccess) return CURDKV_ERR_HIP;
     pl.copy_pending = true;
+    pl.copy_stream = stream;
     std::memcpy(pl.cached.data(), offsets, cmp_bytes);
     pl.valid = true;
     return CURDKV_OK;

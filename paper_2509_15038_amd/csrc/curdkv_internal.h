@@ -35,6 +35,7 @@ struct Plan {
     bool valid = false;
     hipEvent_t copied = nullptr;       // recorded after the last staging -> device copy
     bool copy_pending = false;
+    hipStream_t copy_stream = nullptr; // the stream that copy was queued on
 };
 
 }  // namespace curdkv

@@ -10,6 +10,13 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # test_oracle_mutants.py re-runs the oracle's pins in a child process with one planted
+    # mistake switched on through this variable; it is never set otherwise
+    mutant = os.environ.get("CURDKV_ORACLE_MUTANT")
+    if mutant:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        from oracle_mutants import MUTANTS
+        MUTANTS[mutant]()
 
 
 @pytest.fixture(scope="session")

@@ -55,3 +55,27 @@ def test_value_guided_selection_shrinks_the_lemma1_term():
         # value-only scores retain at least as much value mass as the key-value product
         Sv = orc.select(orc.scores(K, V, G, source="v"), n // 10, 4)
         assert vn[Sv].sum() >= vn[S].sum() * 0.999
+
+
+def test_attention_output_brute_force_and_one_hot():
+    import math
+    rng = np.random.default_rng(4)
+    m, n, d = 3, 5, 4
+    Q, K, V = rng.standard_normal((m, d)), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    want = np.zeros((m, d))
+    for i in range(m):
+        w = [math.exp(sum(Q[i, c] * K[j, c] for c in range(d)) / math.sqrt(d)) for j in range(n)]
+        for j in range(n):
+            for c in range(d):
+                want[i, c] += w[j] / sum(w) * V[j, c]
+    assert np.allclose(ev.attention_output(Q, K, V), want, rtol=1e-12)
+    # a query that matches one key overwhelmingly returns that token's value row
+    K = np.eye(4)[[0, 1, 2, 3, 0]] * 1.0
+    K[4] = 0.0
+    V = rng.standard_normal((5, 4)) * 3.0
+    out = ev.attention_output(200.0 * np.eye(4)[[2]], K, V)
+    assert np.allclose(out[0], V[2], atol=1e-9)
+    # evicting a token no query attends to costs nothing; evicting the attended one does
+    Qh = 200.0 * np.eye(4)[[2]]
+    assert ev.eviction_loss(Qh, K, V, np.array([0, 1, 2, 3])) < 1e-9
+    assert ev.eviction_loss(Qh, K, V, np.array([0, 1, 3, 4])) > 1.0
