@@ -225,8 +225,10 @@ def main():
     }
 
     if args.adaptive is not None:
-        kbase = int(budgets[0])
+        kbase = int(np.sum(budgets) // heads)                   # the per-head budget the layers share out
         bd = torch.empty((heads,), dtype=torch.int32, device="cuda")
+        ia = torch.empty((heads * kbase,), dtype=torch.int32, device="cuda")   # every layer keeps H*kbase rows
+        Ka = torch.empty((heads * kbase, d), dtype=Ko.dtype, device="cuda"); Va = torch.empty_like(Ka)
         bh = torch.empty((heads,), dtype=torch.int32, pin_memory=True)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
         parts = []
@@ -240,18 +242,32 @@ def main():
             torch.cuda.current_stream().synchronize()          # budgets are needed on the host
             ab_ = bh.numpy().copy()
             ao = wl.offsets_for(ab_)
-            ctx.select(scores, n, ab_, s, ao, indices)
+            ctx.select(scores, n, ab_, s, ao, ia)
             ev[3].record()
-            ctx.compact(Kd, Vd, n, indices, ao, Ko, Vo)
+            ctx.compact(Kd, Vd, n, ia, ao, Ka, Va)
             ev[4].record()
             torch.cuda.synchronize()
             if it >= args.warmup:
                 parts.append([ev[j].elapsed_time(ev[j + 1]) for j in range(4)])
         pm = np.array(parts).mean(0)
+        # the same in one call, budgets and offsets staying on the device
+        od = torch.empty((heads + 1,), dtype=torch.int64, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        one = []
+        for it in range(args.warmup + args.steps):
+            e0.record()
+            ctx.compress_adaptive(Kd, Vd, n, kbase, s, args.adaptive, scores, bd, od, ia, Ka, Va)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                one.append(e0.elapsed_time(e1))
+        assert bd.cpu().numpy().tolist() == ab_.tolist()
         out["adaptive"] = {"alpha": args.adaptive, "base_budget": kbase,
                            "ms": {"scores": float(pm[0]), "budgets_incl_copy": float(pm[1]),
                                   "select_incl_host_gap": float(pm[2]), "compact": float(pm[3]),
                                   "total": float(pm.sum())},
+                           "one_call_ms": float(np.mean(one)),
+                           "one_call_frac_of_hbm_peak": ab["total"] / (float(np.mean(one)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                            "budget_min_max": [int(ab_.min()), int(ab_.max())]}
     if args.append:
         raw = torch.empty((heads, n), dtype=torch.float32, device="cuda")

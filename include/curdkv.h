@@ -171,6 +171,25 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
 int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
                             int32_t n_sink, double alpha, int32_t* budgets_out, void* stream);
 
+/* AdaCurDKV in one call with nothing passing through the host (Algorithm 1 with the
+ * head-wise budgets of Section 3.2, "Adaptive budget allocation"): scores as in
+ * curdkv_scores, budgets as in curdkv_adaptive_budgets, their prefix sums, then the
+ * selection and the gather of curdkv_select / curdkv_compact with those budgets,
+ * all enqueued on `stream` without a synchronisation or a copy to the host.
+ * Every layer keeps kv_heads*budget rows, so the sizes are known beforehand:
+ * scores: device float [layers, kv_heads, n], or NULL (library scratch, allocated
+ *   on first need);
+ * budgets_out: device int32 [layers*kv_heads]; offsets_out: device int64
+ *   [layers*kv_heads + 1], offsets_out[i] = budgets_out[0] + .. + budgets_out[i-1];
+ * indices: device int32 [layers*kv_heads*budget]; K_out, V_out: device
+ *   [layers*kv_heads*budget, head_dim]; group i owns rows offsets_out[i] ..
+ *   offsets_out[i+1]-1 of all three, tokens ascending.
+ * 0 <= budget <= n, 0 <= alpha <= 1, n_sink >= 0; kv_heads <= 1024. */
+int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
+                             int32_t budget, int32_t n_sink, double alpha, float* scores,
+                             int32_t* budgets_out, int64_t* offsets_out, int32_t* indices,
+                             void* K_out, void* V_out, void* stream);
+
 /* Scoring during generation (Section 3.2: the method "can be applied during the
  * pre-filling as well as the token generation phase").  The un-normalised scores
  * lKV_j of a token do not depend on the other tokens, so a growing cache is scored

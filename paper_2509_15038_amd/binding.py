@@ -23,7 +23,7 @@ _DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
 
 EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
            "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
-           "curdkv_adaptive_budgets", "curdkv_scores_append", "curdkv_normalise", "curdkv_strerror"]
+           "curdkv_adaptive_budgets", "curdkv_compress_adaptive", "curdkv_scores_append", "curdkv_normalise", "curdkv_strerror"]
 
 
 class CurdkvConfig(C.Structure):
@@ -64,6 +64,7 @@ def lib() -> C.CDLL:
     L.curdkv_compact.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
     L.curdkv_compress.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
     L.curdkv_adaptive_budgets.argtypes = [vp, vp, i64, i32, i32, C.c_double, vp, vp]
+    L.curdkv_compress_adaptive.argtypes = [vp, vp, vp, i64, i32, i32, C.c_double, vp, vp, vp, vp, vp, vp, vp]
     L.curdkv_scores_append.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.curdkv_normalise.argtypes = [vp, vp, vp, i64, i64, vp, vp]
     L.curdkv_strerror.argtypes = [C.c_int]
@@ -200,6 +201,15 @@ class Context:
                                            float(alpha), _ptr(budgets_out), _stream(stream))
         if rc != OK:
             raise CurdkvError(rc, "curdkv_adaptive_budgets")
+
+    def compress_adaptive(self, K, V, n: int, budget: int, n_sink: int, alpha: float, scores,
+                          budgets_out, offsets_out, indices, K_out, V_out, stream=None):
+        rc = lib().curdkv_compress_adaptive(self._h, _ptr(K), _ptr(V), int(n), int(budget), int(n_sink),
+                                            float(alpha), _ptr(scores), _ptr(budgets_out),
+                                            _ptr(offsets_out), _ptr(indices), _ptr(K_out), _ptr(V_out),
+                                            _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_compress_adaptive")
 
     def scores_append(self, K_new, V_new, m: int, n_old: int, stride: int, raw, sums, stream=None):
         rc = lib().curdkv_scores_append(self._h, _ptr(K_new), _ptr(V_new), int(m), int(n_old),

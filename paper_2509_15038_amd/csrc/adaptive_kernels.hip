@@ -195,6 +195,71 @@ __global__ void ada_uniform_kernel(int32_t* __restrict__ budgets, int count, int
     if (i < count) budgets[i] = value;
 }
 
+// ---- offsets and gather block table from budgets that only exist on the device -------------
+// One workgroup walks the heads in order, 1024 at a time.  Prefix sums are kept within
+// [0, total] and the last offset is total, so that whatever the budgets hold, the selection
+// and gather kernels that follow stay inside buffers sized for `total` rows.
+__global__ __launch_bounds__(kAdaThreads) void ada_offsets_kernel(const int32_t* __restrict__ budgets, int heads,
+                                                                  int64_t n, int64_t total,
+                                                                  int64_t* __restrict__ offsets) {
+    __shared__ long long wave_tot[kAdaWaves];
+    __shared__ long long carry_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { carry_s = 0; offsets[0] = 0; }
+    __syncthreads();
+    for (int base = 0; base < heads; base += kAdaThreads) {
+        const int i = base + tid;
+        long long b = i < heads ? (long long)budgets[i] : 0;
+        b = b < 0 ? 0 : (b > n ? n : b);
+        long long incl = b;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const long long t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        long long before = carry_s;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        if (i < heads) {
+            const long long end = before + incl;
+            offsets[i + 1] = (i == heads - 1 || end > total) ? total : end;
+        }
+        __syncthreads();
+        if (tid == kAdaThreads - 1) carry_s = before + incl;
+        __syncthreads();
+    }
+}
+
+// block b of the gather starts at row b*kCompactRowsPerBlock: the head owning that row is the
+// first one whose rows end beyond it
+__global__ void ada_blocks_kernel(const int64_t* __restrict__ offsets, int heads, int64_t blocks,
+                                  BlockInfo* __restrict__ info) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= blocks) return;
+    const int64_t p = b * kCompactRowsPerBlock;
+    int lo = 0, hi = heads - 1;                    // offsets[heads] = total > p, so the answer exists
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (offsets[mid + 1] > p) hi = mid; else lo = mid + 1;
+    }
+    BlockInfo bi;
+    bi.head_end = offsets[lo + 1];
+    bi.head = lo;
+    bi.pad = 0;
+    info[b] = bi;
+}
+
+hipError_t launch_adaptive_plan(const curdkv_ctx* ctx, const int32_t* budgets, int64_t n, int64_t total,
+                                int64_t* offsets, BlockInfo* block_info, hipStream_t stream) {
+    ada_offsets_kernel<<<dim3(1), kAdaThreads, 0, stream>>>(budgets, ctx->heads, n, total, offsets);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || total == 0) return e;
+    const int64_t blocks = (total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
+    ada_blocks_kernel<<<dim3((unsigned)((blocks + 255) / 256)), 256, 0, stream>>>(offsets, ctx->heads, blocks, block_info);
+    return hipGetLastError();
+}
+
 // bits per level so that H histograms fit in 128 KB of LDS
 static int level_bits(int H) {
     int bits = 12;

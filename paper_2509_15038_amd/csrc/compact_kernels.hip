@@ -72,16 +72,17 @@ __global__ __launch_bounds__(256) void compact_kernel(
 
 hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                           const int32_t* indices, const int64_t* d_offsets, int64_t total,
-                          void* K_out, void* V_out, hipStream_t stream) {
+                          void* K_out, void* V_out, hipStream_t stream, const BlockInfo* block_info) {
     if (total == 0) return hipSuccess;
+    if (!block_info) block_info = ctx->plan.d_block_info;
     const int64_t blocks = (total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         compact_kernel<16><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, ctx->plan.d_block_info, total,
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total,
             (u32x4*)K_out, (u32x4*)V_out);
     } else {
         compact_kernel<32><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, ctx->plan.d_block_info, total,
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total,
             (u32x4*)K_out, (u32x4*)V_out);
     }
     return hipGetLastError();

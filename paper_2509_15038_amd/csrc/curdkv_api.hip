@@ -98,6 +98,7 @@ void release(curdkv_ctx* ctx) {
     if (ctx->d_partial) (void)hipFree(ctx->d_partial);
     if (ctx->d_scores_ws) (void)hipFree(ctx->d_scores_ws);
     if (ctx->d_adaptive_ws) (void)hipFree(ctx->d_adaptive_ws);
+    if (ctx->d_adaptive_blocks) (void)hipFree(ctx->d_adaptive_blocks);
     if (ctx->d_zero_offsets) (void)hipFree(ctx->d_zero_offsets);
     if (ctx->plan.d_buf) (void)hipFree(ctx->plan.d_buf);
     if (ctx->plan.h_staging) (void)hipHostFree(ctx->plan.h_staging);
@@ -353,6 +354,59 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
     }
     return launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t budget,
+                             int32_t n_sink, double alpha, float* scores, int32_t* budgets_out,
+                             int64_t* offsets_out, int32_t* indices, void* K_out, void* V_out, void* stream) {
+    if (!ctx || !K || !V || !budgets_out || !offsets_out) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0 || budget < 0 || budget > n) return CURDKV_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return CURDKV_ERR_INVALID_ARG;
+    if (ctx->cfg.kv_heads > 1024) return CURDKV_ERR_UNSUPPORTED;
+    if (((uintptr_t)K | (uintptr_t)V | (uintptr_t)K_out | (uintptr_t)V_out) & 15u) return CURDKV_ERR_INVALID_ARG;
+    const int64_t total = (int64_t)ctx->heads * budget;       // every layer keeps kv_heads*budget rows
+    if (total > 0 && (!indices || !K_out || !V_out)) return CURDKV_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (!scores) {
+        if (!ctx->d_scores_ws &&
+            hipMalloc((void**)&ctx->d_scores_ws, (size_t)ctx->heads * (size_t)ctx->cfg.max_tokens * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->d_scores_ws = nullptr;
+            return CURDKV_ERR_OOM;
+        }
+        scores = ctx->d_scores_ws;
+    }
+    if (!ctx->d_adaptive_ws && hipMalloc(&ctx->d_adaptive_ws, adaptive_workspace_bytes(ctx)) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->d_adaptive_ws = nullptr;
+        return CURDKV_ERR_OOM;
+    }
+    if (!ctx->d_adaptive_blocks &&
+        hipMalloc((void**)&ctx->d_adaptive_blocks, ctx->plan.max_blocks * sizeof(BlockInfo)) != hipSuccess) {
+        (void)hipGetLastError();
+        ctx->d_adaptive_blocks = nullptr;
+        return CURDKV_ERR_OOM;
+    }
+    // normalised scores first: the allocation compares them across the heads of a layer
+    const hipError_t e = fused_applicable(ctx, n)
+        ? launch_fused(ctx, K, V, n, 0, ctx->d_zero_offsets, scores, nullptr, nullptr, nullptr, st)
+        : launch_scores(ctx, K, V, n, scores, st);
+    if (e != hipSuccess) return CURDKV_ERR_HIP;
+    const int64_t sp = n_sink < n ? n_sink : n;
+    int64_t g = (int64_t)std::floor(alpha * (double)budget) - sp;
+    if (g < 0) g = 0;
+    if (g > n - sp) g = n - sp;
+    const long long H = ctx->cfg.kv_heads;
+    const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
+    if (launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out, st) != hipSuccess ||
+        launch_adaptive_plan(ctx, budgets_out, n, total, offsets_out, ctx->d_adaptive_blocks, st) != hipSuccess)
+        return CURDKV_ERR_HIP;
+    if (total == 0) return CURDKV_OK;
+    if (launch_select(ctx, scores, n, n_sink, offsets_out, indices, st) != hipSuccess ||
+        launch_compact(ctx, K, V, n, indices, offsets_out, total, K_out, V_out, st, ctx->d_adaptive_blocks) != hipSuccess)
+        return CURDKV_ERR_HIP;
+    return CURDKV_OK;
 }
 
 int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, int64_t m,

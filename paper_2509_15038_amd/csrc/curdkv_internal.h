@@ -50,6 +50,7 @@ struct curdkv_ctx {
     float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
     int64_t* d_zero_offsets = nullptr; // [heads + 1] zeros: "keep nothing", for the scores-only use of the fused kernel
     void* d_adaptive_ws = nullptr;     // histograms and per-layer state of curdkv_adaptive_budgets, on first use
+    curdkv::BlockInfo* d_adaptive_blocks = nullptr;  // gather block table built on the device (curdkv_compress_adaptive), on first use
     float* d_scores_ws = nullptr;      // [heads, max_tokens], allocated when curdkv_compress needs it
     int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes
     int num_cu = 0;
@@ -85,7 +86,8 @@ hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_
                          int scale_blocks = 0);
 hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                           const int32_t* indices, const int64_t* d_offsets, int64_t total,
-                          void* K_out, void* V_out, hipStream_t stream);
+                          void* K_out, void* V_out, hipStream_t stream,
+                          const BlockInfo* block_info = nullptr);   // default: the table of the host-side plan
 hipError_t configure_kernels(curdkv_ctx* ctx);
 hipError_t configure_select(curdkv_ctx* ctx);
 hipError_t configure_fused(curdkv_ctx* ctx);
@@ -93,6 +95,10 @@ hipError_t configure_adaptive(curdkv_ctx* ctx);
 size_t adaptive_workspace_bytes(const curdkv_ctx* ctx);
 hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t k,
                            int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream);
+// offsets[i] = budgets[0] + .. + budgets[i-1], kept within [0, total] (offsets[heads] = total), and
+// the gather block table for them; everything on the device.
+hipError_t launch_adaptive_plan(const curdkv_ctx* ctx, const int32_t* budgets, int64_t n, int64_t total,
+                                int64_t* offsets, BlockInfo* block_info, hipStream_t stream);
 bool fused_applicable(const curdkv_ctx* ctx, int64_t n);
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,

@@ -311,6 +311,66 @@ def test_adaptive_end_to_end_c3_shape(gu):
                           int(budgets[i]), s, where=f"ada l{l} h{h}")
 
 
+@pytest.mark.parametrize("layers,kv_heads,n,r,dtype", [(16, 8, 3000 + 11, 64, "bf16"),   # fused scoring phases
+                                                        (2, 4, 5000 + 3, 128, "bf16"),   # general kernels
+                                                        (3, 2, 40000 + 1, 32, "bf16"),   # streaming selection
+                                                        (1, 8, 700, 32, "fp32")])
+def test_adaptive_one_call_on_device(gu, layers, kv_heads, n, r, dtype):
+    # scores -> budgets -> offsets -> select -> gather in one call, nothing through the host
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=layers, kv_heads=kv_heads, n=n, r=r, dtype=dtype)
+    K, V = wl.host_cache(cfg)
+    L, H = cfg.layers, cfg.kv_heads
+    heads = L * H
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Kd, Vd = gu.to_device(K, dtype), gu.to_device(V, dtype)
+    with B.Context(L, H, 4, 128, cfg.r, dtype, n, cfg.sketch_seed) as ctx:
+        for (k, s, alpha) in [(n // 10, 4, 0.2), (n // 3, 0, 0.0), (n // 20, 64, 1.0), (3, 4, 0.2), (0, 4, 0.2)]:
+            total = heads * k
+            sc = torch.full((heads, n), float("nan"), dtype=torch.float32, device="cuda")
+            bd = torch.full((heads,), -7, dtype=torch.int32, device="cuda")
+            od = torch.full((heads + 1,), -7, dtype=torch.int64, device="cuda")
+            idx = torch.full((max(total, 1),), -1, dtype=torch.int32, device="cuda")
+            Ko = torch.zeros((max(total, 1), 128), dtype=tdt, device="cuda"); Vo = torch.zeros_like(Ko)
+            ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, sc, bd, od, idx, Ko, Vo)
+            torch.cuda.synchronize()
+            budgets, off, sc_h = bd.cpu().numpy(), od.cpu().numpy(), sc.cpu().numpy()
+            for l in range(L):        # both sides decide on the GPU's fp32 scores
+                want = orc.adaptive_budgets(sc_h[l * H:(l + 1) * H].astype(np.float64), k, s, alpha)
+                assert budgets[l * H:(l + 1) * H].tolist() == want.tolist(), (k, s, alpha, l)
+            assert off.tolist() == wl.offsets_for(budgets).tolist() and off[-1] == total
+            idx_h, Ko_h, Vo_h = idx.cpu().numpy(), gu.to_host(Ko, dtype), gu.to_host(Vo, dtype)
+            for l in range(L):
+                for h in range(H):
+                    i = l * H + h
+                    G = orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, dtype)
+                    a, b = int(off[i]), int(off[i + 1])
+                    gu.check_head(cfg, None, K[l, h], V[l, h], G, sc_h[i], idx_h[a:b], Ko_h[a:b], Vo_h[a:b],
+                                  int(budgets[i]), s, where=f"ada one call k{k} s{s} a{alpha} l{l} h{h}")
+        # without a score buffer of the caller's
+        # (fresh buffers of the right size: the loop above ended with the empty budget)
+        k, s, alpha = n // 10, 4, 0.2
+        idx = torch.empty((heads * k,), dtype=torch.int32, device="cuda")
+        Ko = torch.empty((heads * k, 128), dtype=tdt, device="cuda"); Vo = torch.empty_like(Ko)
+        bd2 = torch.empty((heads,), dtype=torch.int32, device="cuda")
+        od2 = torch.empty((heads + 1,), dtype=torch.int64, device="cuda")
+        idx2 = torch.empty((heads * k,), dtype=torch.int32, device="cuda")
+        Ko2 = torch.empty((heads * k, 128), dtype=tdt, device="cuda"); Vo2 = torch.empty_like(Ko2)
+        ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, sc, bd, od, idx, Ko, Vo)
+        ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, None, bd2, od2, idx2, Ko2, Vo2)
+        torch.cuda.synchronize()
+        assert torch.equal(bd, bd2) and torch.equal(od, od2) and torch.equal(idx, idx2)
+        ity = torch.int16 if dtype == "bf16" else torch.int32
+        assert torch.equal(Ko.view(ity), Ko2.view(ity)) and torch.equal(Vo.view(ity), Vo2.view(ity))
+        # every rejected call returns before anything is launched
+        for args in [(Kd, Vd, n, n + 1, 4, 0.2, sc, bd, od, idx, Ko, Vo), (Kd, Vd, n, 5, 4, 1.2, sc, bd, od, idx, Ko, Vo),
+                     (Kd, Vd, n, 5, 4, 0.2, sc, None, od, idx, Ko, Vo), (Kd, Vd, n, 5, 4, 0.2, sc, bd, None, idx, Ko, Vo),
+                     (Kd, Vd, n, 5, 4, 0.2, sc, bd, od, None, Ko, Vo), (Kd, Vd, n + 1, 5, 4, 0.2, sc, bd, od, idx, Ko, Vo)]:
+            with pytest.raises(B.CurdkvError) as e:
+                ctx.compress_adaptive(*args)
+            assert e.value.code == B.ERR_INVALID_ARG
+
+
 def test_adaptive_budgets_errors(gu):
     import torch
     with B.Context(1, 2, 4, 128, 64, "bf16", 64, 1) as ctx:
