@@ -22,6 +22,10 @@
  *     copy of the offsets, all on the device that was current at curdkv_create;
  *     that device must be current for every later call (else INVALID_ARG).
  *     Calls on one context must not overlap in time on different streams.
+ *   - Capturing a compute call in a HIP graph: run the same call (same offsets,
+ *     same optional buffers) once and synchronise before the capture, so that
+ *     the capture neither uploads offsets nor allocates scratch; both would
+ *     make the call unfit for capture.
  *   - K and V are row-major [layers, kv_heads, n, head_dim] in the context's
  *     storage type; token j of group (l, h) starts at element
  *     ((l*kv_heads + h)*n + j)*head_dim.  Base pointers must be 16-byte aligned.

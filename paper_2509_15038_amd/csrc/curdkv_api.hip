@@ -60,8 +60,14 @@ int sync_offsets(curdkv_ctx* ctx, const int64_t* offsets, const int32_t* budgets
     const size_t cmp_bytes = (size_t)(heads + 1) * sizeof(int64_t);
     if (pl.valid && std::memcmp(pl.cached.data(), offsets, cmp_bytes) == 0) {
         // same offsets as last time; a caller that moved to another stream must still see the copy
-        if (pl.copy_pending && stream != pl.copy_stream &&
-            hipStreamWaitEvent(stream, pl.copied, 0) != hipSuccess) return CURDKV_ERR_HIP;
+        if (pl.copy_pending && stream != pl.copy_stream) {
+            // (a stream under graph capture cannot wait for work outside its graph; callers
+            // that capture have run the same call once, and synchronised, beforehand)
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); cs = hipStreamCaptureStatusActive; }
+            if (cs == hipStreamCaptureStatusNone && hipStreamWaitEvent(stream, pl.copied, 0) != hipSuccess)
+                return CURDKV_ERR_HIP;
+        }
         return CURDKV_OK;
     }
     if (pl.copy_pending) {                       // staging buffer may still be being read

@@ -572,3 +572,57 @@ def test_error_paths_launch_nothing(gu):
     with pytest.raises(B.CurdkvError) as e:
         B.Context(1, 1, 1, 64, 64, "bf16", 16, 1)
     assert e.value.code == B.ERR_UNSUPPORTED
+
+
+# ---- HIP graphs: the compute calls only enqueue kernels, so a graph can hold them ------------
+
+@pytest.mark.parametrize("layers,n,one_call", [(16, 2000 + 17, True), (1, 3000 + 5, True), (2, 1500, False)])
+def test_graph_capture_and_replay(gu, layers, n, one_call):
+    # captured once, replayed on fresh data with eager work and synchronisations in between;
+    # every replay must give, bit for bit, what the eager call gives on the same inputs
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=layers, n=n)
+    heads = layers * cfg.kv_heads
+    budgets = wl.budgets_for(cfg, 0.1)
+    off = wl.offsets_for(budgets)
+    total = int(off[-1])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+
+    def fresh():
+        return (torch.randn((heads, n, 128), device="cuda", generator=gen) *
+                torch.rand((heads, n, 1), device="cuda", generator=gen)).to(torch.bfloat16)
+
+    Kd, Vd = fresh(), fresh()
+    sc = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+    idx = torch.empty((total,), dtype=torch.int32, device="cuda")
+    Ko = torch.empty((total, 128), dtype=torch.bfloat16, device="cuda"); Vo = torch.empty_like(Ko)
+    with B.Context(layers, cfg.kv_heads, 4, 128, cfg.r, "bf16", n, cfg.sketch_seed) as ctx:
+        def call():
+            if one_call:
+                ctx.compress(Kd, Vd, n, budgets, 4, off, sc, idx, Ko, Vo)
+            else:
+                ctx.scores(Kd, Vd, n, sc)
+                ctx.select(sc, n, budgets, 4, off, idx)
+                ctx.compact(Kd, Vd, n, idx, off, Ko, Vo)
+        call()                                   # before the capture: uploads the offsets
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            call()
+        for rep in range(3):
+            Kd.copy_(fresh()); Vd.copy_(fresh())
+            for t in (sc, idx, Ko, Vo):
+                t.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = [t.clone() for t in (sc, idx, Ko.view(torch.int16), Vo.view(torch.int16))]
+            for t in (sc, idx, Ko, Vo):
+                t.zero_()
+            call()
+            torch.cuda.synchronize()
+            for a, b in zip(got, (sc, idx, Ko.view(torch.int16), Vo.view(torch.int16))):
+                assert torch.equal(a, b), rep
+            assert int(idx.max()) < n and float(sc.sum()) > 0.99 * heads
+        del g
