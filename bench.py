@@ -135,8 +135,7 @@ def main():
     ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed, args.source,
                     not args.no_projection)
     s = cfg.n_sink
-    fused = (cfg.dtype == "bf16" and (cfg.r <= 64 or args.no_projection) and n <= 32768
-             and heads >= 128 and total * 5 <= heads * n * 2)
+    fused = ctx.uses_fused_kernel(n) and total * 5 <= heads * n * 2
 
     def step_calls(ev=None):
         if ev:

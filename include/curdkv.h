@@ -145,18 +145,26 @@ int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
 /* The whole of Algorithm 1 in one call: scores, selection and gather, with the
  * results of curdkv_scores + curdkv_select + curdkv_compact (same arguments,
  * same layouts; `scores` may be NULL when the caller does not want them, the
- * library then uses a scratch buffer it allocates on first need).  When a head's
- * scores fit in one compute unit's LDS (bf16, sketch_dim <= 64, n <= 32768) and
- * there are at least half as many (layer, group) pairs as compute units, one
- * fused kernel does everything with one workgroup per pair and the scores never
- * pass through HBM between the steps (when more than 40 % of all rows are kept,
- * only its scoring phases are used and the stand-alone selection and gather
- * kernels follow); otherwise the kernels of the separate calls are launched.  The normalising sum is taken in a
- * different order in the two cases, so scores can differ in the last bits
+ * library then uses a scratch buffer it allocates on first need).  Where
+ * curdkv_uses_fused_kernel says so, one fused kernel does everything with one
+ * workgroup per (layer, group) and the scores never pass through HBM between
+ * the steps (when more than 40 % of all rows are kept, only its scoring phases
+ * are used and the stand-alone selection and gather kernels follow); otherwise
+ * the kernels of the separate calls are launched.  The normalising sum is taken
+ * in a different order in the two cases, so scores can differ in the last bits
  * between them. */
 int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                     const int32_t* budgets, int32_t n_sink, const int64_t* offsets,
                     float* scores, int32_t* indices, void* K_out, void* V_out, void* stream);
+
+/* Which kernels curdkv_scores / curdkv_compress launch for a cache of n tokens
+ * per head: 1 = the fused one-workgroup-per-head kernel, 0 = the general
+ * kernels; negative = error code.  The fused kernel needs bf16, a sketch of at
+ * most 64 columns (or no projection), n <= 32768, and a number of (layer,
+ * group) pairs that fills whole rounds of the GPU's compute units to at least
+ * 90 %.  The results are the same either way (Algorithm 1); the entry exists so
+ * that tests and tuning know which path they exercise. */
+int curdkv_uses_fused_kernel(const curdkv_ctx* ctx, int64_t n);
 
 /* AdaCurDKV head-wise budgets (Section 3.2, "Adaptive budget allocation"): every
  * layer keeps kv_heads*budget tokens in all, the top normalised scores ACROSS the

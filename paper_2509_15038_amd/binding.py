@@ -22,7 +22,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 _DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
 
 EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
-           "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
+           "curdkv_uses_fused_kernel", "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
            "curdkv_adaptive_budgets", "curdkv_compress_adaptive", "curdkv_scores_append", "curdkv_normalise", "curdkv_strerror"]
 
 
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
     L.curdkv_destroy.argtypes = [vp]
     L.curdkv_sketch_host.argtypes = [cfgp, i32, i32, vp]
     L.curdkv_set_sketch.argtypes = [vp, i32, i32, vp]
+    L.curdkv_uses_fused_kernel.argtypes = [vp, i64]
     L.curdkv_scores.argtypes = [vp, vp, vp, i64, vp, vp]
     L.curdkv_fold.argtypes = [vp, vp, i64, vp, vp]
     L.curdkv_select.argtypes = [vp, vp, i64, vp, i32, vp, vp, vp]
@@ -194,6 +195,12 @@ class Context:
                                    _ptr(K_out), _ptr(V_out), _stream(stream))
         if rc != OK:
             raise CurdkvError(rc, "curdkv_compress")
+
+    def uses_fused_kernel(self, n: int) -> bool:
+        rc = lib().curdkv_uses_fused_kernel(self._h, int(n))
+        if rc < 0:
+            raise CurdkvError(rc, "curdkv_uses_fused_kernel")
+        return bool(rc)
 
     def adaptive_budgets(self, scores, n: int, budget: int, n_sink: int, alpha: float, budgets_out,
                          stream=None):

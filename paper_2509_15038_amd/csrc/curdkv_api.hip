@@ -241,6 +241,11 @@ int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float*
     return rc;
 }
 
+int curdkv_uses_fused_kernel(const curdkv_ctx* ctx, int64_t n) {
+    if (!ctx || n < 1 || n > ctx->cfg.max_tokens) return CURDKV_ERR_INVALID_ARG;
+    return fused_applicable(ctx, n) ? 1 : 0;
+}
+
 int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, float* scores,
                   void* stream) {
     if (!ctx || !K || !V || !scores) return CURDKV_ERR_INVALID_ARG;

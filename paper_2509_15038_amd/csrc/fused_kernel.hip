@@ -181,7 +181,12 @@ bool fused_applicable(const curdkv_ctx* ctx, int64_t n) {
     if (n > 64 * kFusedThreads) return false;
     const size_t lds = (((size_t)n + 63) & ~(size_t)63) * 4 + sizeof(SelectShared<kFusedThreads, 64>) + 1024;
     if (lds > (size_t)ctx->lds_limit) return false;
-    return 2 * ctx->heads >= ctx->num_cu;
+    // One workgroup per head and one workgroup per CU at a time: the heads go through the chip
+    // in rounds of num_cu, and a last round that is mostly empty costs a full scan time.  Measured
+    // at n = 32768: 256, 512, 768 heads are faster fused; 128, 288, 384, 640 heads are faster
+    // with the general kernels, 192 is a tie.
+    const int64_t rounds = (ctx->heads + ctx->num_cu - 1) / ctx->num_cu;
+    return (int64_t)ctx->heads * 10 >= rounds * ctx->num_cu * 9;
 }
 
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,

@@ -88,8 +88,9 @@ def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="
 
 
 def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None,
-                  one_call: bool = False, source: str = "kv", projection: bool = True):
-    """Whole path on a host cache, every head compared with the oracle."""
+                  one_call: bool = False, source: str = "kv", projection: bool = True, fused=None):
+    """Whole path on a host cache, every head compared with the oracle.  fused = True / False
+    additionally asserts which kernels the library says it launches for this shape."""
     s = cfg.n_sink if n_sink is None else n_sink
     if K is None:
         K, V = wl.host_cache(cfg)
@@ -97,6 +98,8 @@ def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=No
     Kd, Vd = to_device(K, cfg.dtype), to_device(V, cfg.dtype)
     worst, ndiff = 0.0, 0
     with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed, source, projection) as ctx:
+        if fused is not None:
+            assert ctx.uses_fused_kernel(n) == fused, f"{cfg.name}: expected fused={fused} for {L * H} heads, n={n}"
         sc, idx, Ko, Vo, off = run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype, one_call)
         sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
         Ko_h, Vo_h = to_host(Ko, cfg.dtype), to_host(Vo, cfg.dtype)

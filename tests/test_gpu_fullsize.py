@@ -24,12 +24,14 @@ def _announce(request):
     yield
 
 
-def _full(cfg, keeps, sample, gu, one_call=False):
+def _full(cfg, keeps, sample, gu, one_call=False, fused=None):
     import torch
     L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
     heads = L * H
     Kd, Vd = wl.device_cache(cfg)
     with B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
+        if fused is not None:
+            assert ctx.uses_fused_kernel(n) == fused
         for keep in keeps:
             budgets = wl.budgets_for(cfg, keep)
             print(f"  {cfg.name} n={n} keep={keep} total rows={int(budgets.sum())}", flush=True)
@@ -95,16 +97,16 @@ def test_c3_quarter_model_three_kernels(gu):
     # 64 heads are too few for the one-workgroup-per-head kernel: stand-alone scoring,
     # normalisation, selection and gather kernels at n = 32768
     cfg = wl.scaled(wl.CONFIGS["c3"], layers=8)
-    _full(cfg, (0.10, 0.50), [(0, 0), (7, 7)], gu)
-    _full(cfg, (0.20,), [(3, 4)], gu, one_call=True)
+    _full(cfg, (0.10, 0.50), [(0, 0), (7, 7)], gu, fused=False)
+    _full(cfg, (0.20,), [(3, 4)], gu, one_call=True, fused=False)
 
 
 def test_c3_full_one_call_fused(gu):
-    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu, one_call=True)
+    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu, one_call=True, fused=True)
 
 
 def test_c4_full_one_call_fused(gu):
-    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu, one_call=True)
+    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu, one_call=True, fused=True)
 
 
 def test_c4_full_mistral_32k_prefix(gu):

@@ -147,53 +147,56 @@ def test_select_large_n_streaming_ties(gu, n):
         assert np.array_equal(idx[off[h]:off[h + 1]], want), h
 
 
-# ---- the one-call entry point; with >= 128 heads it runs the fused kernel ------------
+# ---- the one-call entry point; with 256 heads (one per CU) it runs the fused kernel ----
 
 @pytest.mark.parametrize("keep", [0.10, 0.50])
 def test_one_call_fused_c3_shape(gu, keep):
-    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=2000 + 17)        # 128 heads, ragged n
-    gu.run_and_check(cfg, wl.budgets_for(cfg, keep), one_call=True)
+    cfg = wl.scaled(wl.CONFIGS["c3"], n=2000 + 17)                   # 256 heads, ragged n
+    gu.run_and_check(cfg, wl.budgets_for(cfg, keep), one_call=True, fused=True)
 
 
 def test_one_call_fused_long_heads(gu):
-    cfg = wl.scaled(wl.CONFIGS["c4"], layers=16, n=16384 + 2048 + 33)  # second key-count variant
-    gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True)
+    cfg = wl.scaled(wl.CONFIGS["c4"], n=16384 + 2048 + 33)           # second key-count variant
+    gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True, fused=True)
 
 
 @pytest.mark.parametrize("r", [20, 32, 64])
 def test_one_call_fused_sketch_dims(gu, r):
-    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=700, r=r)
-    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.2), one_call=True)
+    cfg = wl.scaled(wl.CONFIGS["c3"], n=700, r=r)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.2), one_call=True, fused=True)
 
 
 def test_one_call_fused_degenerate_budgets_and_sinks(gu):
-    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=300)
+    cfg = wl.scaled(wl.CONFIGS["c3"], n=300)
     n = cfg.n
     rng = np.random.default_rng(21)
-    b = rng.choice(np.array([0, 1, 3, 4, 5, 77, n - 1, n], dtype=np.int32), size=128)
+    b = rng.choice(np.array([0, 1, 3, 4, 5, 77, n - 1, n], dtype=np.int32), size=256)
     for s in (4, 0, 64, n + 5):
-        gu.run_and_check(cfg, b, n_sink=s, one_call=True)
-    gu.run_and_check(cfg, np.zeros(128, dtype=np.int32), one_call=True)
+        gu.run_and_check(cfg, b, n_sink=s, one_call=True, fused=True)
+    gu.run_and_check(cfg, np.zeros(256, dtype=np.int32), one_call=True, fused=True)
 
 
 def test_one_call_fused_zero_cache_and_ties(gu):
-    cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=500)
+    cfg = wl.scaled(wl.CONFIGS["c3"], n=500)
     K, V = wl.host_cache(cfg)
     K[3] = 0                                         # a whole layer of zero keys: uniform scores, all tied
     V[5, 2, 100:] = V[5, 2, 100]                     # many identical value rows
     K[5, 2, 100:] = K[5, 2, 100]
-    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.3), K=K, V=V, one_call=True)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.3), K=K, V=V, one_call=True, fused=True)
 
 
 def test_one_call_without_scores_and_fallback_paths(gu):
     import torch
-    # few heads -> the three kernels; n above the LDS limit -> the three kernels; fp32 too
+    # few heads, heads that would leave the second round of CUs mostly empty, n above the LDS
+    # limit, fp32: the three kernels
     for cfg in (wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=900),
+                wl.scaled(wl.CONFIGS["c3"], layers=16, n=400),
+                wl.scaled(wl.CONFIGS["c3"], layers=36, n=200),
                 wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=2, n=40000),
                 wl.CONFIGS["c1"]):
-        gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True)
+        gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True, fused=False)
     # scores = NULL on both paths: indices and rows must equal the run that returned scores
-    for cfg in (wl.scaled(wl.CONFIGS["c3"], layers=16, n=1000), wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=1000)):
+    for cfg in (wl.scaled(wl.CONFIGS["c3"], n=1000), wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=1000)):
         K, V = wl.host_cache(cfg)
         Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
         b = wl.budgets_for(cfg, 0.2); off = wl.offsets_for(b); tot = int(off[-1])
@@ -217,8 +220,9 @@ def test_ablation_variants(gu, source, projection):
     small = wl.scaled(wl.CONFIGS["c2"], kv_heads=3, n=1500 + 7)               # three kernels
     gu.run_and_check(small, wl.budgets_for(small), source=source, projection=projection)
     gu.run_and_check(small, wl.budgets_for(small), source=source, projection=projection, one_call=True)
-    fused = wl.scaled(wl.CONFIGS["c3"], layers=16, n=900 + 5)                 # fused kernel
-    gu.run_and_check(fused, wl.budgets_for(fused, 0.2), source=source, projection=projection, one_call=True)
+    fused = wl.scaled(wl.CONFIGS["c3"], n=900 + 5)                            # fused kernel
+    gu.run_and_check(fused, wl.budgets_for(fused, 0.2), source=source, projection=projection, one_call=True,
+                     fused=True)
     if projection:
         wide = wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=2, n=2000, dirichlet_total_frac=None)   # r = 128
         gu.run_and_check(wide, wl.budgets_for(wide, 0.1), source=source)
@@ -311,7 +315,7 @@ def test_adaptive_end_to_end_c3_shape(gu):
                           int(budgets[i]), s, where=f"ada l{l} h{h}")
 
 
-@pytest.mark.parametrize("layers,kv_heads,n,r,dtype", [(16, 8, 3000 + 11, 64, "bf16"),   # fused scoring phases
+@pytest.mark.parametrize("layers,kv_heads,n,r,dtype", [(32, 8, 2000 + 11, 64, "bf16"),   # fused scoring phases
                                                         (2, 4, 5000 + 3, 128, "bf16"),   # general kernels
                                                         (3, 2, 40000 + 1, 32, "bf16"),   # streaming selection
                                                         (1, 8, 700, 32, "fp32")])
@@ -448,10 +452,10 @@ def test_random_small_shapes_both_paths(gu):
         gu.run_and_check(cfg, b, n_sink=s, one_call=bool(case % 2))
     for case in range(6):                                  # enough heads for the fused kernel
         n = int(rng.integers(1, 400)); r = int(rng.choice([20, 32, 64])); s = int(rng.choice([0, 4, 50]))
-        cfg = wl.scaled(wl.CONFIGS["c3"], layers=16, n=n, r=r)
-        b = rng.integers(0, n + 1, size=128).astype(np.int32)
+        cfg = wl.scaled(wl.CONFIGS["c3"], n=n, r=r)
+        b = rng.integers(0, n + 1, size=256).astype(np.int32)
         print(f"  fused case {case}: n{n} r{r} s{s}", flush=True)
-        gu.run_and_check(cfg, b, n_sink=s, one_call=True)
+        gu.run_and_check(cfg, b, n_sink=s, one_call=True, fused=True)
 
 
 @pytest.mark.parametrize("n", [5000, 33000, 50000])
@@ -576,7 +580,7 @@ def test_error_paths_launch_nothing(gu):
 
 # ---- HIP graphs: the compute calls only enqueue kernels, so a graph can hold them ------------
 
-@pytest.mark.parametrize("layers,n,one_call", [(16, 2000 + 17, True), (1, 3000 + 5, True), (2, 1500, False)])
+@pytest.mark.parametrize("layers,n,one_call", [(32, 2000 + 17, True), (1, 3000 + 5, True), (2, 1500, False)])
 def test_graph_capture_and_replay(gu, layers, n, one_call):
     # captured once, replayed on fresh data with eager work and synchronisations in between;
     # every replay must give, bit for bit, what the eager call gives on the same inputs
