@@ -120,3 +120,12 @@ def test_c5_full_128k_dirichlet(gu):
     l_big = int(np.argmax(b.max(1)))
     sample = [(l_small, int(np.argmin(b[l_small]))), (l_big, int(np.argmax(b[l_big]))), (31, 7)]
     _full(cfg, (None,), sample, gu)
+
+
+def test_million_token_heads(gu):
+    # far beyond the benchmark's contexts: n = 1,000,003 per head (eight of the streaming
+    # selection's compaction blocks, a ragged last tile), every head against the oracle
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=1, kv_heads=2, n=1_000_003)
+    budgets = np.array([50_000, 333_334], dtype=np.int32)
+    worst, _ = gu.run_and_check(cfg, budgets, one_call=True, fused=False)
+    assert worst < 1e-4
