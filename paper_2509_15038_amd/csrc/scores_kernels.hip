@@ -34,15 +34,23 @@ __device__ __forceinline__ void block_partial_store(float wave_total, float* dst
 // ---------------------------------------------------------------------------
 // bf16 storage.  Each wave scores a contiguous range of tiles (scan_device.h),
 // collecting the scores in its own slice of LDS, and writes them out in one
-// burst per kStageTiles tiles: no global store sits inside the streaming loop.
+// burst per stage: no global store sits inside the streaming loop.  Score
+// writes that mingle with the read streams of other waves are dear on this
+// memory system (1 % of the bytes cost 7 % of the time with 8 KB stages), so the
+// stages are as large as LDS allows, normally a wave's whole range, and the
+// stores are non-temporal: the workgroups of one round then end, and write,
+// at about the same time.
 // ---------------------------------------------------------------------------
-constexpr int kStageTiles = 64;     // tiles (of 32 tokens) a wave collects between bursts: 8 KB
+template <int CB> struct Stage {    // tiles (of 32 tokens) a wave collects between bursts
+    static constexpr int kTiles = CB > 4 ? 256 : 128;     // one workgroup per CU: 128 KB; two: 64 KB each
+};
 
 template <int CB, int SRC, bool PROJ>
 __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
     int64_t out_stride, int64_t out_offset) {
+    constexpr int kStageTiles = Stage<CB>::kTiles;
     __shared__ float stage[4][kStageTiles * kTileTokens];
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
@@ -68,7 +76,7 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
         const int32_t r0 = seg * kTileTokens;
         acc_sum += scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane);
         const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
-        for (int32_t r = r0 + lane; r < r1; r += 64) sh[r] = mine[r - r0];
+        for (int32_t r = r0 + lane; r < r1; r += 64) __builtin_nontemporal_store(mine[r - r0], &sh[r]);
     }
     block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
 }
@@ -173,14 +181,33 @@ __global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
     }
 }
 
+// Workgroups per head.  A workgroup should be long-lived (its start-up and the pipeline fill
+// are paid per workgroup) and write its scores once, at its end, so the lower bound is what
+// makes a wave's share fit its LDS stage.  Above that, the smallest count is taken that fills
+// the rounds in which the workgroups pass through the chip to within 3 % of the best
+// (measured at n = 32768: 2 per head for 256 heads, 4 for 128 and 384, 7-8 for 288).
 static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
-    int64_t want = (8LL * ctx->num_cu + ctx->heads - 1) / ctx->heads;   // ~8 blocks per CU in total (measured best of 2, 8, 16)
+    const bool wide = ctx->cfg.dtype == CURDKV_DTYPE_BF16 && ctx->col_blocks > 2 && !ctx->cfg.no_projection;
+    const int64_t stage = wide ? Stage<8>::kTiles : Stage<4>::kTiles;
+    const int64_t slots = (int64_t)ctx->num_cu * (wide ? 1 : 2);      // workgroups resident at a time
     int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
-    if (want > cap) want = cap;
-    if (want > kMaxBlocksPerHead) want = kMaxBlocksPerHead;
-    if (want < 1) want = 1;
-    return (int)want;
+    if (cap > kMaxBlocksPerHead) cap = kMaxBlocksPerHead;
+    int64_t lo = (tiles + 4 * stage - 1) / (4 * stage);
+    if (lo > cap) lo = cap;
+    if (lo < 1) lo = 1;
+    const int64_t hi = lo + 15 < cap ? lo + 15 : cap;
+    auto cost = [&](int64_t b) {                                       // rounds x tiles a wave works through
+        const int64_t rounds = ((int64_t)ctx->heads * b + slots - 1) / slots;
+        int64_t per_wave = (tiles + 4 * b - 1) / (4 * b);
+        per_wave += per_wave & 1;                                      // whole pairs, as in the kernel
+        return rounds * per_wave;
+    };
+    int64_t best = cost(lo);
+    for (int64_t b = lo + 1; b <= hi; ++b) best = cost(b) < best ? cost(b) : best;
+    for (int64_t b = lo; b <= hi; ++b)
+        if (cost(b) * 100 <= best * 103) return (int)b;
+    return (int)lo;
 }
 
 hipError_t configure_kernels(curdkv_ctx* ctx) {
