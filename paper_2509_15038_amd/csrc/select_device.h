@@ -236,16 +236,21 @@ __device__ __forceinline__ void select_core(uint32_t (&x)[KPT], int32_t n, int32
         }
     }
     __syncthreads();
-    // one thread per word writes out that word's tokens, ascending
-    for (int w = tid; w < kWords; w += THREADS) {
-        uint64_t m = sm.gmask[w];
-        uint32_t pos = sm.wpos[w];
+    // a thread lists the kept tokens of a quarter word (16 tokens), ascending.  Quarter words
+    // rather than words bound the walk when the kept tokens are neighbours (sink-like prefixes,
+    // recent windows): 60 neighbours in one word cost one thread, and everybody waiting for
+    // it, 5 us.
+    for (int q = tid; q < kWords * 4; q += THREADS) {
+        const int w = q >> 2, part = q & 3;
+        const uint64_t word = sm.gmask[w];
+        uint32_t m = (uint32_t)(word >> (16 * part)) & 0xFFFFu;
+        uint32_t pos = sm.wpos[w] + (uint32_t)__popcll(word & ((1ull << (16 * part)) - 1ull));
         while (m) {
-            const int bit = __ffsll((unsigned long long)m) - 1;
+            const int bit = __ffs(m) - 1;
             m &= m - 1;
             // positions stay below k by construction; the comparison keeps a write inside
             // the group's slice whatever the keys were
-            if (pos < (uint32_t)k) put(pos, w * 64 + bit);
+            if (pos < (uint32_t)k) put(pos, w * 64 + 16 * part + bit);
             ++pos;
         }
     }

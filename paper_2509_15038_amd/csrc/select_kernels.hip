@@ -270,15 +270,17 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
         __syncthreads();
         eq_carry = sm.carry[0];
         pos_carry = sm.carry[1];
-        for (int w = tid; w < words; w += kSelThreads) {
-            uint64_t m = sm.gmask[w];
-            uint32_t pos = sm.wpos[w];
+        for (int q = tid; q < words * 4; q += kSelThreads) {   // a thread per quarter word (16 tokens)
+            const int w = q >> 2, part = q & 3;
+            const uint64_t word = sm.gmask[w];
+            uint32_t m = (uint32_t)(word >> (16 * part)) & 0xFFFFu;
+            uint32_t pos = sm.wpos[w] + (uint32_t)__popcll(word & ((1ull << (16 * part)) - 1ull));
             while (m) {
-                const int bit = __ffsll((unsigned long long)m) - 1;
+                const int bit = __ffs(m) - 1;
                 m &= m - 1;
                 // positions stay below k by construction; the comparison keeps a write inside
                 // the group's slice even if the scores were changed under the kernel
-                if ((int64_t)pos < k) out[pos] = (int32_t)(super_base + (int64_t)w * 64 + bit);
+                if ((int64_t)pos < k) out[pos] = (int32_t)(super_base + (int64_t)w * 64 + 16 * part + bit);
                 ++pos;
             }
         }
