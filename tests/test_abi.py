@@ -65,3 +65,42 @@ def test_config_validation_on_host():
     assert B.lib().curdkv_sketch_host(C.byref(cfg), 1, 0, G.ctypes.data) == B.ERR_INVALID_ARG
     assert B.lib().curdkv_sketch_host(C.byref(cfg), 0, 0, None) == B.ERR_INVALID_ARG
     assert B.lib().curdkv_sketch_host(None, 0, 0, G.ctypes.data) == B.ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and a C program must
+    # be able to link against the library and call its host-only entry points
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_curdkv.c"
+    src.write_text(r'''
+#include "curdkv.h"
+#include <stdio.h>
+#include <string.h>
+int main(void) {
+    curdkv_config cfg;
+    static float G[128 * 64];
+    unsigned bits;
+    int i;
+    memset(&cfg, 0, sizeof cfg);
+    cfg.layers = 3; cfg.kv_heads = 8; cfg.group_size = 4; cfg.head_dim = 128; cfg.sketch_dim = 64;
+    cfg.dtype = CURDKV_DTYPE_BF16; cfg.max_tokens = 1024; cfg.seed = 0xC0DE0003u;
+    if (curdkv_sketch_host(&cfg, 2, 7, G) != CURDKV_OK) return 1;
+    for (i = 0; i < 6; ++i) { memcpy(&bits, &G[i * 1000], 4); printf("%08x\n", bits); }
+    cfg.head_dim = 96;
+    printf("%d %s\n", curdkv_sketch_host(&cfg, 0, 0, G), curdkv_strerror(CURDKV_ERR_UNSUPPORTED));
+    return 0;
+}
+''')
+    pkg = os.path.join(ROOT, "paper_2509_15038_amd")
+    exe = tmp_path / "use_curdkv"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", pkg, "-lcurdkv", f"-Wl,-rpath,{pkg}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    want = orc.sketch(0xC0DE0003, 2, 7, 8, 128, 64, "bf16").astype(np.float32).reshape(-1)
+    for i in range(6):
+        assert int(out[i], 16) == int(want[i * 1000].view(np.uint32)), i
+    assert out[6].startswith(f"{B.ERR_UNSUPPORTED} unsupported")
