@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the CurDKV selection path on one MI355X.
 
-A step is one pass of the whole hot path -- curdkv_scores, curdkv_select,
-curdkv_compact back to back on one stream -- over a synthetic Llama-3-8B-shaped
+A step is one pass of the whole hot path -- scores, selection and gather, through
+the one-call entry point curdkv_compress -- over a synthetic Llama-3-8B-shaped
 cache (32 layers x 8 KV heads x 32768 tokens x d=128, bf16, r=64) that is already
-resident in HBM.  Prints one JSON line.
+resident in HBM.  The same work as three separate calls (curdkv_scores,
+curdkv_select, curdkv_compact back to back on one stream) is timed as well and
+reported under "three_calls".  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3] [--keep 0.10]
 """
