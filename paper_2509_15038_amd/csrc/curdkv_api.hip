@@ -429,8 +429,11 @@ int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, 
     if (((uintptr_t)K_new | (uintptr_t)V_new) & 15u) return CURDKV_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     int bph = 0;
-    if (launch_scores(ctx, K_new, V_new, m, raw, st, /*normalise=*/false, &bph, stride, n_old) != hipSuccess)
+    bool summed = false;
+    if (launch_scores(ctx, K_new, V_new, m, raw, st, /*normalise=*/false, &bph, stride, n_old, sums,
+                      n_old == 0, &summed) != hipSuccess)
         return CURDKV_ERR_HIP;
+    if (summed) return CURDKV_OK;                 // few new tokens: one launch does it all
     return launch_accumulate(ctx, bph, sums, n_old == 0, st) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 

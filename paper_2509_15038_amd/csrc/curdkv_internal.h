@@ -71,7 +71,11 @@ size_t packed_elems(int col_blocks);
 // sums in ctx->d_partial (*blocks_per_head of them per head) for launch_select to scale.
 hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                          float* scores, hipStream_t stream, bool normalise = true,
-                         int* blocks_per_head = nullptr, int64_t out_stride = 0, int64_t out_offset = 0);
+                         int* blocks_per_head = nullptr, int64_t out_stride = 0, int64_t out_offset = 0,
+                         double* sums = nullptr, bool restart = false, bool* summed = nullptr);
+// sums (device, [heads]) given: where one block scores a whole head, the kernel itself adds the
+// head's total to sums[head] (after zeroing it if `restart`) and *summed is set; otherwise the
+// caller adds the partial sums (launch_accumulate).
 hipError_t launch_accumulate(const curdkv_ctx* ctx, int blocks_per_head, double* sums, bool reset,
                              hipStream_t stream);
 hipError_t launch_normalise_sums(const curdkv_ctx* ctx, const float* raw, const double* sums,

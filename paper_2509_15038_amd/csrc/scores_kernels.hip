@@ -22,13 +22,20 @@ __device__ __forceinline__ float sum_sq(const f32x16& a) {
     return s;
 }
 
-// Sum the four wave totals of a 256-thread block in a fixed order and store it.
-__device__ __forceinline__ void block_partial_store(float wave_total, float* dst) {
+// Sum the four wave totals of a 256-thread block in a fixed order and store it.  A head
+// scored by a single block (few new tokens during generation) can fold the total into the
+// head's running sum right here: sum = (restart ? 0 : sum) + total, in double, which is
+// what accumulate_sums_kernel computes from one partial.
+__device__ __forceinline__ void block_partial_store(float wave_total, float* dst, double* running, int restart) {
     __shared__ float wsum[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (lane == 0) wsum[wave] = wave_total;
     __syncthreads();
-    if (threadIdx.x == 0) *dst = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    if (threadIdx.x == 0) {
+        const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        *dst = total;
+        if (running) *running = (restart ? 0.0 : *running) + (double)total;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -49,7 +56,7 @@ template <int CB, int SRC, bool PROJ>
 __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
-    int64_t out_stride, int64_t out_offset) {
+    int64_t out_stride, int64_t out_offset, double* __restrict__ sums, int restart) {
     constexpr int kStageTiles = Stage<CB>::kTiles;
     __shared__ float stage[4][kStageTiles * kTileTokens];
     const int head = blockIdx.x / blocks_per_head;
@@ -78,7 +85,8 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
         const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
         for (int32_t r = r0 + lane; r < r1; r += 64) __builtin_nontemporal_store(mine[r - r0], &sh[r]);
     }
-    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
+    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk,
+                        sums ? sums + head : nullptr, restart);
 }
 
 // ---------------------------------------------------------------------------
@@ -89,7 +97,7 @@ template <int CB>
 __global__ __launch_bounds__(256) void scores_f32_kernel(
     const float4* __restrict__ K, const float4* __restrict__ V, const float* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
-    int source, int64_t out_stride, int64_t out_offset) {
+    int source, int64_t out_stride, int64_t out_offset, double* __restrict__ sums, int restart) {
     extern __shared__ float gs[];                      // [CB][64 steps][64 lanes]
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
@@ -139,7 +147,8 @@ __global__ __launch_bounds__(256) void scores_f32_kernel(
             acc_sum += lkv;
         }
     }
-    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk);
+    block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk,
+                        sums ? sums + head : nullptr, restart);
 }
 
 // ---------------------------------------------------------------------------
@@ -226,16 +235,20 @@ hipError_t configure_kernels(curdkv_ctx* ctx) {
 
 hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                          float* scores, hipStream_t stream, bool normalise, int* blocks_per_head,
-                         int64_t out_stride, int64_t out_offset) {
+                         int64_t out_stride, int64_t out_offset, double* sums, bool restart,
+                         bool* summed) {
     if (out_stride <= 0) out_stride = n;
     const int bph = pick_blocks_per_head(ctx, n);
     if (blocks_per_head) *blocks_per_head = bph;
+    if (bph != 1) sums = nullptr;                 // several blocks per head: the caller adds the partials
+    if (summed) *summed = sums != nullptr;
+    const int rs = restart ? 1 : 0;
     const dim3 grid((unsigned)(ctx->heads * bph)), block(256);
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         const uint4* k = (const uint4*)K; const uint4* v = (const uint4*)V; const uint4* g = (const uint4*)ctx->d_G;
         float* part = ctx->d_partial;
 #define CURDKV_LAUNCH(CBV, SRCV, PROJV) \
-    scores_bf16_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset)
+    scores_bf16_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset, sums, rs)
 #define CURDKV_BY_SRC(CBV, PROJV)                                                   \
     switch (ctx->cfg.score_source) {                                                \
         case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK, PROJV); break;             \
@@ -258,9 +271,9 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
         const size_t lds = (size_t)ctx->col_blocks * 4096 * 4;
         const int src = ctx->cfg.score_source;
         switch (ctx->col_blocks) {
-            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
-            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
-            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset); break;
+            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
+            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
+            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
         }
     }
     hipError_t e = hipGetLastError();
