@@ -26,6 +26,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+# what plain streaming kernels reach on this chip (measured once with hand-written read and copy
+# kernels over 4 GiB; not re-measured here): context for the fraction of the vendor peak
+READ_CEILING_GBS = 6150.0
+COPY_CEILING_GBS = 5600.0
 
 
 def algorithmic_bytes(cfg, budgets, esize=2, source="kv"):
@@ -221,7 +225,12 @@ def main():
                      "frac": kern_gbs / HBM_PEAK_GBS,
                      "traffic": measured_traffic(cfg.name, keep, fused)
                      if args.source == "kv" and not args.no_projection else None,
-                     "algorithmic_bytes_per_launch": ab["total"], "avg_ms": kern_ms},
+                     "algorithmic_bytes_per_launch": ab["total"], "avg_ms": kern_ms,
+                     "measured_stream_ceilings_GBps": {"read_only": READ_CEILING_GBS, "copy": COPY_CEILING_GBS},
+                     # time the same bytes would take at those ceilings: scan bytes at the read
+                     # ceiling, everything else (scores, indices, gathered rows) at the copy ceiling
+                     "frac_of_stream_ceiling": (ab["scan"] / READ_CEILING_GBS + (ab["total"] - ab["scan"]) / COPY_CEILING_GBS)
+                                               / 1e9 / (kern_ms * 1e-3)},
         "three_calls": calls,
     }
 
