@@ -37,8 +37,9 @@ def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, d
     scores = torch.empty((heads, n), dtype=torch.float32, device="cuda")
     indices = torch.full((max(total, 1),), -7, dtype=torch.int32, device="cuda")
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
-    Ko = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
-    Vo = torch.empty((max(total, 1), 128), dtype=tdt, device="cuda")
+    # (filled with NaN bit patterns: a row that is left out cannot hide behind stale memory)
+    Ko = torch.full((max(total, 1), 128), float("nan"), dtype=tdt, device="cuda")
+    Vo = torch.full((max(total, 1), 128), float("nan"), dtype=tdt, device="cuda")
     if one_call:
         ctx.compress(Kd, Vd, n, budgets, n_sink, offsets, scores, indices, Ko, Vo)
     else:
