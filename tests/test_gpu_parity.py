@@ -630,3 +630,51 @@ def test_graph_capture_and_replay(gu, layers, n, one_call):
                 assert torch.equal(a, b), rep
             assert int(idx.max()) < n and float(sc.sum()) > 0.99 * heads
         del g
+
+
+# ---- one context reused: smaller n than max_tokens, changing budgets, other streams, two contexts ----
+
+def test_context_reuse_changing_sizes_budgets_and_streams(gu):
+    import torch
+    big = wl.scaled(wl.CONFIGS["c3"], layers=2, kv_heads=4, n=3000)
+    other = wl.scaled(wl.CONFIGS["c4"], layers=1, kv_heads=3, n=777, r=32)
+    Kb, Vb = wl.host_cache(big)
+    Ko_, Vo_ = wl.host_cache(other)
+    side = torch.cuda.Stream()
+    rng = np.random.default_rng(77)
+    with B.Context(2, 4, 4, 128, big.r, "bf16", big.n, big.sketch_seed) as ctx, \
+         B.Context(1, 3, 4, 128, other.r, "bf16", 1000, other.sketch_seed) as ctx2:
+        def run(c, cfg, K, V, n, budgets, s, stream, one_call):
+            # the first n tokens of every head, contiguous
+            Kd = gu.to_device(np.ascontiguousarray(K[:, :, :n]), "bf16")
+            Vd = gu.to_device(np.ascontiguousarray(V[:, :, :n]), "bf16")
+            heads = cfg.layers * cfg.kv_heads
+            off = wl.offsets_for(budgets); tot = int(off[-1])
+            sc = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+            idx = torch.full((max(tot, 1),), -1, dtype=torch.int32, device="cuda")
+            Ko = torch.full((max(tot, 1), 128), float("nan"), dtype=torch.bfloat16, device="cuda"); Vo = Ko.clone()
+            torch.cuda.synchronize()
+            st = stream if stream is not None else torch.cuda.current_stream()
+            if one_call:
+                c.compress(Kd, Vd, n, budgets, s, off, sc, idx, Ko, Vo, stream=st)
+            else:
+                c.scores(Kd, Vd, n, sc, stream=st)
+                c.select(sc, n, budgets, s, off, idx, stream=st)
+                c.compact(Kd, Vd, n, idx, off, Ko, Vo, stream=st)
+            st.synchronize()
+            sc_h, idx_h, Ko_h, Vo_h = sc.cpu().numpy(), idx.cpu().numpy(), gu.to_host(Ko, "bf16"), gu.to_host(Vo, "bf16")
+            for l in range(cfg.layers):
+                for h in range(cfg.kv_heads):
+                    i = l * cfg.kv_heads + h
+                    G = orc.sketch(cfg.sketch_seed, l, h, cfg.kv_heads, 128, cfg.r, "bf16")
+                    a, b = int(off[i]), int(off[i + 1])
+                    gu.check_head(cfg, None, K[l, h, :n], V[l, h, :n], G, sc_h[i], idx_h[a:b], Ko_h[a:b], Vo_h[a:b],
+                                  int(budgets[i]), s, where=f"reuse n={n} l{l} h{h}")
+        uniform = np.full(8, 300, dtype=np.int32)
+        for step in range(10):
+            n = int(rng.choice([big.n, 1234, 64, 2999, 1]))
+            budgets = uniform.clip(max=n) if step % 3 == 0 else rng.integers(0, n + 1, size=8).astype(np.int32)
+            run(ctx, big, Kb, Vb, n, budgets, int(rng.choice([0, 4, 64])), side if step % 2 else None, bool(step % 4 < 2))
+            if step % 3 == 1:                    # the other context in between, its own plan and sketches
+                n2 = int(rng.choice([other.n, 100]))
+                run(ctx2, other, Ko_, Vo_, n2, rng.integers(0, n2 + 1, size=3).astype(np.int32), 4, None, True)
