@@ -259,13 +259,26 @@ def adaptive_budgets(lt: np.ndarray, k: int, s: int, alpha: float) -> np.ndarray
     most n - s').  The remaining R = H*(k - s') - H*g places go to the largest
     scores among all non-sink, non-safe tokens of the layer; equal scores are
     taken in (head, token) order.  k <= s' leaves nothing to allot: k per head."""
+    budgets, _ = _adaptive_allot(lt, k, s, alpha)
+    return budgets
+
+
+def adaptive_cut_score(lt: np.ndarray, k: int, s: int, alpha: float):
+    """The smallest score that `adaptive_budgets` admits in its layer-wide step (the score of
+    the last of the R places), or None when that step has nothing to allot.  Tests use it to
+    tell which tokens sit so close to the cut that fp32 scores may order them differently."""
+    _, cut = _adaptive_allot(lt, k, s, alpha)
+    return cut
+
+
+def _adaptive_allot(lt: np.ndarray, k: int, s: int, alpha: float):
     lt = np.asarray(lt, dtype=np.float64)
     H, n = lt.shape
     if not (0 <= k <= n) or s < 0 or not (0.0 <= alpha <= 1.0):
         raise ValueError("need 0 <= k <= n, s >= 0, 0 <= alpha <= 1")
     sp = min(s, n)
     if k <= sp:
-        return np.full(H, k, dtype=np.int64)
+        return np.full(H, k, dtype=np.int64), None
     g = min(max(int(np.floor(alpha * k)) - sp, 0), n - sp)
     R = H * (k - sp) - H * g
     cand = lt[:, sp:]
@@ -278,7 +291,8 @@ def adaptive_budgets(lt: np.ndarray, k: int, s: int, alpha: float) -> np.ndarray
     head_of = np.broadcast_to(rows, cand.shape)[open_]        # (head, token) order
     picked = np.argsort(-cand[open_], kind="stable")[:R]
     extra = np.bincount(head_of[picked], minlength=H)
-    return (sp + g + extra).astype(np.int64)
+    cut = float(cand[open_][picked[-1]]) if R > 0 else None
+    return (sp + g + extra).astype(np.int64), cut
 
 
 def compact(K: np.ndarray, V: np.ndarray, S: np.ndarray):

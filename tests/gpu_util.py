@@ -88,6 +88,29 @@ def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="
     return rel, ndiff
 
 
+def check_adaptive_budgets(got: np.ndarray, lt: np.ndarray, k: int, s: int, alpha: float, where=""):
+    """Head-wise budgets of one layer against the oracle's, which are computed from the
+    oracle's own float64 scores lt [H, n].  The GPU decides on its fp32 scores, so the two may
+    disagree about tokens whose oracle score is within RTOL (relative) of the oracle's cut
+    score: a head's budget may differ by at most the number of its tokens in that band, the
+    layer's total and the safeguard must hold exactly."""
+    H, n = lt.shape
+    want = orc.adaptive_budgets(lt, k, s, alpha)
+    assert got.shape == want.shape and int(got.sum()) == int(want.sum()), f"{where}: layer total"
+    sp = min(s, n)
+    if k > sp:
+        g = min(max(int(np.floor(alpha * k)) - sp, 0), n - sp)
+        assert got.min() >= sp + g, f"{where}: safeguard"
+    if np.array_equal(got, want):
+        return 0
+    cut = orc.adaptive_cut_score(lt, k, s, alpha)
+    assert cut is not None, f"{where}: budgets differ although nothing is allotted layer-wide"
+    band = np.sum(np.abs(lt[:, sp:] - cut) <= RTOL * cut, axis=1)
+    assert np.all(np.abs(got.astype(np.int64) - want) <= band), \
+        f"{where}: budgets {got.tolist()} vs {want.tolist()}, near-cut tokens per head {band.tolist()}"
+    return int(np.abs(got.astype(np.int64) - want).sum())
+
+
 def run_and_check(cfg: wl.Config, budgets: np.ndarray, n_sink=None, K=None, V=None,
                   one_call: bool = False, source: str = "kv", projection: bool = True, fused=None):
     """Whole path on a host cache, every head compared with the oracle.  fused = True / False

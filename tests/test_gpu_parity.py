@@ -293,10 +293,11 @@ def test_adaptive_end_to_end_c3_shape(gu):
         torch.cuda.synchronize()
         budgets = bd.cpu().numpy()
         sc_h = sc.cpu().numpy()
-        # the allocation is checked on the GPU's own fp32 scores (both sides decide on the same numbers)
+        # the allocation against the oracle's, made from the oracle's own scores
         for l in range(L):
-            want = orc.adaptive_budgets(sc_h[l * H:(l + 1) * H].astype(np.float64), k, s, alpha)
-            assert budgets[l * H:(l + 1) * H].tolist() == want.tolist()
+            lt = np.stack([orc.scores(orc.to_f64(K[l, h], "bf16"), orc.to_f64(V[l, h], "bf16"),
+                                      orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, "bf16")) for h in range(H)])
+            gu.check_adaptive_budgets(budgets[l * H:(l + 1) * H], lt, k, s, alpha, where=f"layer {l}")
         assert np.all(budgets.reshape(L, H).sum(1) == H * k) and budgets.min() >= int(alpha * k)
         assert len(set(budgets.tolist())) > 1                                   # it does adapt
         off = wl.offsets_for(budgets)
@@ -328,6 +329,9 @@ def test_adaptive_one_call_on_device(gu, layers, kv_heads, n, r, dtype):
     heads = L * H
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     Kd, Vd = gu.to_device(K, dtype), gu.to_device(V, dtype)
+    lt_layers = [np.stack([orc.scores(orc.to_f64(K[l, h], dtype), orc.to_f64(V[l, h], dtype),
+                                      orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, dtype)) for h in range(H)])
+                 for l in range(L)]
     with B.Context(L, H, 4, 128, cfg.r, dtype, n, cfg.sketch_seed) as ctx:
         for (k, s, alpha) in [(n // 10, 4, 0.2), (n // 3, 0, 0.0), (n // 20, 64, 1.0), (3, 4, 0.2), (0, 4, 0.2)]:
             total = heads * k
@@ -339,9 +343,9 @@ def test_adaptive_one_call_on_device(gu, layers, kv_heads, n, r, dtype):
             ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, sc, bd, od, idx, Ko, Vo)
             torch.cuda.synchronize()
             budgets, off, sc_h = bd.cpu().numpy(), od.cpu().numpy(), sc.cpu().numpy()
-            for l in range(L):        # both sides decide on the GPU's fp32 scores
-                want = orc.adaptive_budgets(sc_h[l * H:(l + 1) * H].astype(np.float64), k, s, alpha)
-                assert budgets[l * H:(l + 1) * H].tolist() == want.tolist(), (k, s, alpha, l)
+            for l in range(L):        # against the oracle's allocation, made from the oracle's own scores
+                gu.check_adaptive_budgets(budgets[l * H:(l + 1) * H], lt_layers[l], k, s, alpha,
+                                          where=f"k{k} s{s} a{alpha} layer {l}")
             assert off.tolist() == wl.offsets_for(budgets).tolist() and off[-1] == total
             idx_h, Ko_h, Vo_h = idx.cpu().numpy(), gu.to_host(Ko, dtype), gu.to_host(Vo, dtype)
             for l in range(L):
