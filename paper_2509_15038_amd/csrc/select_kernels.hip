@@ -9,6 +9,7 @@ namespace curdkv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelStaticReserve = 24 * 1024;            // LDS kept for the kernels' static arrays
 // ---------------------------------------------------------------------------
 // Streaming variant for n too large for the register-resident one.  The head's
 // scores (a few hundred KB, resident in L2 / Infinity Cache after the scoring
@@ -337,8 +338,12 @@ template <int KPT>
 static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, int32_t n_sink,
                              const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
                              int scale_blocks) {
+    // the staging area takes what the kernel's static LDS leaves, within the dynamic size the
+    // kernel was configured for (configure_select); indices beyond it go straight to memory
     const size_t fixed = sizeof(SelectShared<kSelThreads, KPT>) + 256;
     int64_t cap = ((int64_t)ctx->lds_limit - (int64_t)fixed) / 4;
+    const int64_t configured = ((int64_t)ctx->lds_limit - kSelStaticReserve) / 4;
+    if (cap > configured) cap = configured;
     if (cap > n) cap = n;
     if (cap < 0) cap = 0;
     select_reg_kernel<KPT><<<dim3((unsigned)ctx->heads), kSelThreads, (size_t)cap * 4, stream>>>(
@@ -347,7 +352,7 @@ static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, in
 }
 
 hipError_t configure_select(curdkv_ctx* ctx) {
-    const int dyn = ctx->lds_limit - 24 * 1024;      // what the kernels' static LDS leaves
+    const int dyn = ctx->lds_limit - kSelStaticReserve;   // what the kernels' static LDS leaves
     if (dyn <= 48 * 1024) return hipSuccess;
     hipError_t e;
     e = hipFuncSetAttribute((const void*)select_reg_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, dyn);

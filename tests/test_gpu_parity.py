@@ -462,7 +462,7 @@ def test_random_small_shapes_both_paths(gu):
         gu.run_and_check(cfg, b, n_sink=s, one_call=True, fused=True)
 
 
-@pytest.mark.parametrize("n", [5000, 33000, 50000])
+@pytest.mark.parametrize("n", [5000, 33000, 36000, 36864, 50000])
 def test_select_adversarial_scores(gu, n):
     # huge dynamic range, denormals, zeros, blocks of duplicates straddling the cut: every
     # variant of the selection kernel (registers for n <= 36864, streaming above) must agree
