@@ -682,3 +682,63 @@ def test_context_reuse_changing_sizes_budgets_and_streams(gu):
             if step % 3 == 1:                    # the other context in between, its own plan and sketches
                 n2 = int(rng.choice([other.n, 100]))
                 run(ctx2, other, Ko_, Vo_, n2, rng.integers(0, n2 + 1, size=3).astype(np.int32), 4, None, True)
+
+
+def test_generation_loop_compress_append_compress(gu):
+    # Section 3.2: compression during generation.  A cache is compressed after the prompt, grows
+    # token by token, and is compressed again whenever it passes a limit; the library scores only
+    # the new rows each step and re-scores the kept rows after a compression.  The oracle runs
+    # the same loop on its own copy of the cache, re-scoring everything each time.
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c2"], layers=1, kv_heads=4, n=1100)
+    K, V = wl.host_cache(cfg)                                   # the token stream: prompt, then generated tokens
+    H, cap, limit, keep, s = 4, 1024, 320, 256, 4
+    prompt = 600
+    Gs = [orc.sketch(cfg.sketch_seed, 0, h, H, 128, cfg.r, "bf16") for h in range(H)]
+    # oracle's cache, per head: arrays of rows (storage bits)
+    oK = [K[0, h, :prompt].copy() for h in range(H)]
+    oV = [V[0, h, :prompt].copy() for h in range(H)]
+    with B.Context(1, H, 4, 128, cfg.r, "bf16", cap, cfg.sketch_seed) as ctx:
+        Kc = torch.zeros((H, cap, 128), dtype=torch.bfloat16, device="cuda"); Vc = torch.zeros_like(Kc)
+        raw = torch.zeros((H, cap), dtype=torch.float32, device="cuda")
+        sums = torch.zeros((H,), dtype=torch.float64, device="cuda")
+        n = prompt
+        Kc[:, :n] = gu.to_device(np.ascontiguousarray(K[0, :, :n]), "bf16")
+        Vc[:, :n] = gu.to_device(np.ascontiguousarray(V[0, :, :n]), "bf16")
+        ctx.scores_append(Kc[:, :n].contiguous(), Vc[:, :n].contiguous(), n, 0, cap, raw, sums)
+        nxt, compressions = prompt, 0
+        while True:
+            if n >= limit:                                      # ---- compress to `keep` tokens per head
+                budgets = np.full(H, keep, dtype=np.int32); off = wl.offsets_for(budgets)
+                Kd, Vd = Kc[:, :n].contiguous(), Vc[:, :n].contiguous()
+                sc = torch.empty((H, n), dtype=torch.float32, device="cuda")
+                idx = torch.empty((H * keep,), dtype=torch.int32, device="cuda")
+                Ko = torch.full((H * keep, 128), float("nan"), dtype=torch.bfloat16, device="cuda"); Vo = Ko.clone()
+                ctx.normalise(raw, sums, cap, n, sc)
+                ctx.select(sc, n, budgets, s, off, idx)
+                ctx.compact(Kd, Vd, n, idx, off, Ko, Vo)
+                torch.cuda.synchronize()
+                sc_h, idx_h = sc.cpu().numpy(), idx.cpu().numpy()
+                Ko_h, Vo_h = gu.to_host(Ko, "bf16"), gu.to_host(Vo, "bf16")
+                for h in range(H):
+                    a, b = h * keep, (h + 1) * keep
+                    _, nd = gu.check_head(cfg, None, oK[h], oV[h], Gs[h], sc_h[h], idx_h[a:b], Ko_h[a:b], Vo_h[a:b],
+                                          keep, s, where=f"generation loop, compression {compressions}, head {h}")
+                    assert nd == 0, "a near-cut difference: the two caches would part ways (pick another seed)"
+                    S = orc.select(orc.scores(orc.to_f64(oK[h], "bf16"), orc.to_f64(oV[h], "bf16"), Gs[h]), keep, s)
+                    oK[h], oV[h] = orc.compact(oK[h], oV[h], S)
+                n = keep
+                Kc[:, :n] = Ko.view(H, keep, 128); Vc[:, :n] = Vo.view(H, keep, 128)
+                ctx.scores_append(Kc[:, :n].contiguous(), Vc[:, :n].contiguous(), n, 0, cap, raw, sums)   # kept rows, afresh
+                compressions += 1
+                if compressions == 4:
+                    break
+            m = 1 if (nxt % 7) else 5                           # mostly single tokens, now and then a few
+            Kn = gu.to_device(np.ascontiguousarray(K[0, :, nxt:nxt + m]), "bf16")
+            Vn = gu.to_device(np.ascontiguousarray(V[0, :, nxt:nxt + m]), "bf16")
+            Kc[:, n:n + m] = Kn; Vc[:, n:n + m] = Vn
+            ctx.scores_append(Kn, Vn, m, n, cap, raw, sums)
+            for h in range(H):
+                oK[h] = np.concatenate([oK[h], K[0, h, nxt:nxt + m]]); oV[h] = np.concatenate([oV[h], V[0, h, nxt:nxt + m]])
+            n += m; nxt += m
+        assert nxt > prompt + 150 and compressions == 4
