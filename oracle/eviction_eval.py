@@ -40,3 +40,31 @@ def lemma1_sides(Q: np.ndarray, K: np.ndarray, V: np.ndarray, S: np.ndarray):
     lhs = np.linalg.norm(softmax_rows(Q @ K.T) @ V - softmax_rows(Q @ Kp.T) @ Vp)
     rhs = np.sqrt(n) * np.linalg.norm(V - Vp) + 2.0 * np.sqrt(n) * np.linalg.norm(Vp)
     return float(lhs), float(rhs)
+
+
+def selection_policies(K: np.ndarray, V: np.ndarray, scores_kv: np.ndarray, k: int, s: int,
+                       rng: np.random.Generator) -> dict:
+    """Index sets of k tokens (the first s always kept) under the selection the paper proposes
+    and under the simple policies it is compared with in spirit: `curdkv` takes the given
+    CurDKV scores, `key_norm` / `value_norm` the squared row norms of K / V alone, `random` a
+    uniform draw.  Ascending indices.  (The paper's baselines proper -- SnapKV, ChunkKV, Knorm,
+    StreamingLLM -- need attention weights or their own code and are out of scope.)"""
+    n = K.shape[0]
+    s = min(s, k, n)
+
+    def top(score):
+        order = np.argsort(-score[s:], kind="stable")[: k - s] + s
+        return np.sort(np.concatenate([np.arange(s), order]))
+
+    return {
+        "curdkv": top(np.asarray(scores_kv, dtype=np.float64)),
+        "key_norm": top(np.sum(K * K, axis=1)),
+        "value_norm": top(np.sum(V * V, axis=1)),
+        "random": np.sort(np.concatenate([np.arange(s), rng.choice(np.arange(s, n), size=k - s, replace=False)])),
+    }
+
+
+def compare_policies(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scores_kv: np.ndarray, k: int, s: int,
+                     rng: np.random.Generator) -> dict:
+    """Eviction loss || attn(Q,K,V) - attn(Q,K[S],V[S]) ||_F of each policy's index set."""
+    return {name: eviction_loss(Q, K, V, S) for name, S in selection_policies(K, V, scores_kv, k, s, rng).items()}

@@ -79,3 +79,29 @@ def test_attention_output_brute_force_and_one_hot():
     Qh = 200.0 * np.eye(4)[[2]]
     assert ev.eviction_loss(Qh, K, V, np.array([0, 1, 2, 3])) < 1e-9
     assert ev.eviction_loss(Qh, K, V, np.array([0, 1, 3, 4])) > 1.0
+
+
+def test_policy_comparison_harness():
+    # the harness itself: every policy keeps k tokens with the sinks, costs nothing at k = n,
+    # and (averaged over heads) loses less the more it keeps.  No claim about which policy
+    # wins on synthetic queries is made or tested.
+    rng = np.random.default_rng(5)
+    losses = {}
+    for seed in range(4):
+        K, V = _head(200 + seed, 512)
+        n = K.shape[0]
+        G = orc.sketch(6, seed, 0, 1, 128, 32, "bf16")
+        lt = orc.scores(K, V, G)
+        Q = K[rng.choice(n, 16, replace=False)] * 0.5 + rng.standard_normal((16, 128)) * 0.5   # queries near some keys
+        for k in (32, 128, 384, n):
+            sets = ev.selection_policies(K, V, lt, k, 4, rng)
+            for name, S in sets.items():
+                assert S.shape == (k,) and np.all(np.diff(S) > 0) and np.array_equal(S[:4], np.arange(4)), name
+            assert np.array_equal(sets["curdkv"], orc.select(lt, k, 4))
+            for name, loss in ev.compare_policies(Q, K, V, lt, k, 4, rng).items():
+                losses.setdefault((name, k), []).append(loss)
+                if k == n:
+                    assert loss < 1e-9
+    for name in ("curdkv", "key_norm", "value_norm", "random"):
+        mean = [np.mean(losses[(name, k)]) for k in (32, 128, 384, 512)]
+        assert mean[0] > mean[2] > mean[3], (name, mean)
