@@ -104,3 +104,15 @@ int main(void) {
     for i in range(6):
         assert int(out[i], 16) == int(want[i * 1000].view(np.uint32)), i
     assert out[6].startswith(f"{B.ERR_UNSUPPORTED} unsupported")
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    # no CPU fallback: without the built library every use of the binding raises
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libcurdkv.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+    with pytest.raises(RuntimeError):
+        B.Context(1, 1, 1, 128, 32, "bf16", 16, 1)
+    with pytest.raises(RuntimeError):
+        B.strerror(0)
