@@ -742,3 +742,48 @@ def test_generation_loop_compress_append_compress(gu):
                 oK[h] = np.concatenate([oK[h], K[0, h, nxt:nxt + m]]); oV[h] = np.concatenate([oV[h], V[0, h, nxt:nxt + m]])
             n += m; nxt += m
         assert nxt > prompt + 150 and compressions == 4
+
+
+def test_graph_capture_adaptive_one_call(gu):
+    # the adaptive one-call path is nine launches and no host round trip: it fits a graph too
+    import torch
+    layers, H, n, k = 4, 8, 2500, 300
+    heads = layers * H
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(9)
+
+    def fresh():
+        return (torch.randn((heads, n, 128), device="cuda", generator=gen) *
+                torch.rand((heads, n, 1), device="cuda", generator=gen)).to(torch.bfloat16)
+
+    Kd, Vd = fresh(), fresh()
+    sc = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+    bd = torch.empty((heads,), dtype=torch.int32, device="cuda")
+    od = torch.empty((heads + 1,), dtype=torch.int64, device="cuda")
+    idx = torch.empty((heads * k,), dtype=torch.int32, device="cuda")
+    Ko = torch.empty((heads * k, 128), dtype=torch.bfloat16, device="cuda"); Vo = torch.empty_like(Ko)
+    outs = (sc, bd, od, idx, Ko, Vo)
+    with B.Context(layers, H, 4, 128, 64, "bf16", n, 3) as ctx:
+        def call():
+            ctx.compress_adaptive(Kd, Vd, n, k, 4, 0.2, sc, bd, od, idx, Ko, Vo)
+        call()                                   # before the capture: allocates the workspaces
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            call()
+        for rep in range(3):
+            Kd.copy_(fresh()); Vd.copy_(fresh())
+            for t in outs:
+                t.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = [t.clone() for t in (sc, bd, od, idx, Ko.view(torch.int16), Vo.view(torch.int16))]
+            for t in outs:
+                t.zero_()
+            call()
+            torch.cuda.synchronize()
+            for a, b in zip(got, (sc, bd, od, idx, Ko.view(torch.int16), Vo.view(torch.int16))):
+                assert torch.equal(a, b), rep
+            assert int(od[-1]) == heads * k and len(set(bd.tolist())) > 1
+        del g
