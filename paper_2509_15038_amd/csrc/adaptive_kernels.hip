@@ -76,15 +76,17 @@ __global__ __launch_bounds__(kAdaThreads) void ada_hist_kernel(
     for (int i = tid; i < NB; i += kAdaThreads) dst[i] = hist[i];
 }
 
+constexpr int kAdaHeadsAtOnce = 8;
+
 struct AdaShared {
-    uint32_t wave_tot[kAdaWaves];
+    uint32_t wave_tot[kAdaHeadsAtOnce][kAdaWaves];
     unsigned long long best;                      // first position (bins counted from the top) reaching R
 };
 
 __global__ __launch_bounds__(kAdaThreads) void ada_resolve_kernel(
     const uint32_t* __restrict__ ws_hist, int H, int decided, int B, int32_t sp, int32_t g, long long R,
     AdaLayerState* __restrict__ state, uint32_t* __restrict__ ws_above, int32_t* __restrict__ budgets) {
-    extern __shared__ uint32_t dyn[];
+    extern __shared__ __align__(16) uint32_t dyn[];
     const int NB = 1 << B;
     uint32_t* hist = dyn;                          // [H][NB]
     uint32_t* above = dyn + (size_t)H * NB;        // [H] keys above the prefix decided so far
@@ -93,52 +95,93 @@ __global__ __launch_bounds__(kAdaThreads) void ada_resolve_kernel(
 
     const int layer = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int h = 0; h < H; ++h) {
-        const uint32_t* src = ws_hist + ((size_t)layer * H + h) * kAdaMaxBins;
-        for (int i = tid; i < NB; i += kAdaThreads) hist[(size_t)h * NB + i] = src[i];
+    {   // the H histograms, 16 bytes per load and eight loads in flight per thread (one load at a
+        // time, each waited for, made this copy most of the kernel's 25 us); NB >= 4
+        const int quads = (H * NB) >> 2;
+        constexpr int kInFlight = 8;
+        for (int q0 = tid; q0 < quads; q0 += kInFlight * kAdaThreads) {
+            uint4 v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int q = q0 + u * kAdaThreads;
+                const int e = (q < quads ? q : q0) << 2;              // element number h*NB + i
+                const int h = e >> B, i = e & (NB - 1);
+                v[u] = *reinterpret_cast<const uint4*>(ws_hist + ((size_t)layer * H + h) * kAdaMaxBins + i);
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int q = q0 + u * kAdaThreads;
+                if (q < quads) *reinterpret_cast<uint4*>(hist + ((size_t)q << 2)) = v[u];
+            }
+        }
     }
     for (int h = tid; h < H; h += kAdaThreads) above[h] = decided ? ws_above[(size_t)layer * H + h] : 0u;
     if (tid == 0) sm.best = ~0ull;
     __syncthreads();
 
     // ---- find the bin where sum_h max(0, c_h - g) reaches R ---------------------------------
+    // kAdaHeadsAtOnce heads go through the workgroup-wide prefix sums together, so a layer of
+    // eight heads costs one barrier instead of sixteen (the kernel is latency-bound: one
+    // workgroup per layer).
     const int per = NB >= kAdaThreads ? NB / kAdaThreads : 1;           // bins per thread, from the top
     unsigned long long E[4] = {0, 0, 0, 0};
-    for (int h = 0; h < H; ++h) {
-        uint32_t c[4], tot = 0;
+    for (int h0 = 0; h0 < H; h0 += kAdaHeadsAtOnce) {
+        uint32_t c[kAdaHeadsAtOnce][4], tot[kAdaHeadsAtOnce], incl[kAdaHeadsAtOnce];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int pos = tid * per + i;
-            c[i] = (i < per && pos < NB) ? hist[(size_t)h * NB + (NB - 1 - pos)] : 0u;
-            tot += c[i];
-        }
-        uint32_t incl = tot;
+        for (int j = 0; j < kAdaHeadsAtOnce; ++j) {
+            const int h = h0 + j;
+            tot[j] = 0;
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
+            for (int i = 0; i < 4; ++i) {
+                const int pos = tid * per + i;
+                c[j][i] = (h < H && i < per && pos < NB) ? hist[(size_t)h * NB + (NB - 1 - pos)] : 0u;
+                tot[j] += c[j][i];
+            }
+            incl[j] = tot[j];
         }
-        if (lane == 63) sm.wave_tot[wave] = incl;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1)
+#pragma unroll
+            for (int j = 0; j < kAdaHeadsAtOnce; ++j) {
+                const uint32_t t = __shfl_up(incl[j], off, 64);
+                if (lane >= off) incl[j] += t;
+            }
+        if (lane == 63) {
+#pragma unroll
+            for (int j = 0; j < kAdaHeadsAtOnce; ++j) sm.wave_tot[j][wave] = incl[j];
+        }
         __syncthreads();
-        uint32_t before = 0;
-        for (int w = 0; w < wave; ++w) before += sm.wave_tot[w];
-        if (lane == 0) wave_excl[h * kAdaWaves + wave] = before;
-        uint32_t run = above[h] + before + incl - tot;          // keys of head h in higher bins
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            run += c[i];
-            if (i < per && run > (uint32_t)g) E[i] += run - (uint32_t)g;
+        for (int j = 0; j < kAdaHeadsAtOnce; ++j) {
+            const int h = h0 + j;
+            if (h >= H) break;
+            uint32_t before = 0;
+            for (int w = 0; w < wave; ++w) before += sm.wave_tot[j][w];
+            if (lane == 0) wave_excl[h * kAdaWaves + wave] = before;
+            uint32_t run = above[h] + before + incl[j] - tot[j];       // keys of head h in higher bins
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                run += c[j][i];
+                if (i < per && run > (uint32_t)g) E[i] += run - (uint32_t)g;
+            }
         }
-        __syncthreads();                                        // wave_tot is reused by the next head
+        __syncthreads();                                        // wave_tot is reused by the next heads
     }
     {
-        unsigned long long mine = ~0ull;
+        // E grows with the position, so every thread beyond the crossing qualifies: the minimum is
+        // taken inside each wave first, one atomic per wave instead of one per thread
+        uint32_t mine = 0xFFFFFFFFu;
 #pragma unroll
         for (int i = 3; i >= 0; --i) {
             const int pos = tid * per + i;
-            if (i < per && pos < NB && E[i] >= (unsigned long long)R) mine = (unsigned long long)pos;
+            if (i < per && pos < NB && E[i] >= (unsigned long long)R) mine = (uint32_t)pos;
         }
-        if (mine != ~0ull) atomicMin(&sm.best, mine);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t o = __shfl_xor(mine, off, 64);
+            mine = o < mine ? o : mine;
+        }
+        if (lane == 0 && mine != 0xFFFFFFFFu) atomicMin(&sm.best, (unsigned long long)mine);
     }
     __syncthreads();
     const int best = (int)sm.best;                              // exists: the lowest bin reaches R
@@ -199,9 +242,12 @@ __global__ void ada_uniform_kernel(int32_t* __restrict__ budgets, int count, int
 // One workgroup walks the heads in order, 1024 at a time.  Prefix sums are kept within
 // [0, total] and the last offset is total, so that whatever the budgets hold, the selection
 // and gather kernels that follow stay inside buffers sized for `total` rows.
+__device__ __forceinline__ void ada_block_entry(const int64_t* offsets, int heads, int64_t b, BlockInfo* info);
+
 __global__ __launch_bounds__(kAdaThreads) void ada_offsets_kernel(const int32_t* __restrict__ budgets, int heads,
                                                                   int64_t n, int64_t total,
-                                                                  int64_t* __restrict__ offsets) {
+                                                                  int64_t* offsets,      // written, then read back below
+                                                                  int64_t blocks_here, BlockInfo* info) {
     __shared__ long long wave_tot[kAdaWaves];
     __shared__ long long carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -229,14 +275,13 @@ __global__ __launch_bounds__(kAdaThreads) void ada_offsets_kernel(const int32_t*
         if (tid == kAdaThreads - 1) carry_s = before + incl;
         __syncthreads();
     }
+    // a table of moderate size is filled right here (blocks_here = 0: a launch of its own does it)
+    for (int64_t b = tid; b < blocks_here; b += kAdaThreads) ada_block_entry(offsets, heads, b, info);
 }
 
 // block b of the gather starts at row b*kCompactRowsPerBlock: the head owning that row is the
 // first one whose rows end beyond it
-__global__ void ada_blocks_kernel(const int64_t* __restrict__ offsets, int heads, int64_t blocks,
-                                  BlockInfo* __restrict__ info) {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= blocks) return;
+__device__ __forceinline__ void ada_block_entry(const int64_t* offsets, int heads, int64_t b, BlockInfo* info) {
     const int64_t p = b * kCompactRowsPerBlock;
     int lo = 0, hi = heads - 1;                    // offsets[heads] = total > p, so the answer exists
     while (lo < hi) {
@@ -250,12 +295,22 @@ __global__ void ada_blocks_kernel(const int64_t* __restrict__ offsets, int heads
     info[b] = bi;
 }
 
+__global__ void ada_blocks_kernel(const int64_t* __restrict__ offsets, int heads, int64_t blocks,
+                                  BlockInfo* __restrict__ info) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < blocks) ada_block_entry(offsets, heads, b, info);
+}
+
 hipError_t launch_adaptive_plan(const curdkv_ctx* ctx, const int32_t* budgets, int64_t n, int64_t total,
                                 int64_t* offsets, BlockInfo* block_info, hipStream_t stream) {
-    ada_offsets_kernel<<<dim3(1), kAdaThreads, 0, stream>>>(budgets, ctx->heads, n, total, offsets);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || total == 0) return e;
     const int64_t blocks = (total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
+    // a table of one entry per thread is filled by the offsets kernel itself; a longer one by a
+    // launch of its own (one workgroup walking 6552 entries took 10 us, the extra launch 5)
+    const bool small = blocks <= kAdaThreads;
+    ada_offsets_kernel<<<dim3(1), kAdaThreads, 0, stream>>>(budgets, ctx->heads, n, total, offsets,
+                                                           small ? blocks : 0, block_info);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || small) return e;
     ada_blocks_kernel<<<dim3((unsigned)((blocks + 255) / 256)), 256, 0, stream>>>(offsets, ctx->heads, blocks, block_info);
     return hipGetLastError();
 }
