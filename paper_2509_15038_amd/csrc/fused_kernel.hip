@@ -153,11 +153,31 @@ static hipError_t by_source(const FusedArgs& a, int source) {
     }
 }
 
+template <int CB, bool PROJ>
+static hipError_t by_keys(const FusedArgs& a, int kpt, int source) {
+    switch (kpt) {
+        case 4: return by_source<CB, 4, PROJ>(a, source);
+        case 8: return by_source<CB, 8, PROJ>(a, source);
+        case 16: return by_source<CB, 16, PROJ>(a, source);
+        case 32: return by_source<CB, 32, PROJ>(a, source);
+        default: return by_source<CB, 64, PROJ>(a, source);
+    }
+}
+
+// keys per thread in the selection: the smallest of 4, 8, 16, 32, 64 that covers n with 512 threads
+// (every pass of the selection walks all of a thread's keys, present or not)
+static int keys_per_thread(int64_t n) {
+    for (int kpt = 4; kpt < 64; kpt *= 2)
+        if (n <= (int64_t)kpt * kFusedThreads) return kpt;
+    return 64;
+}
+constexpr int kKeyVariants[5] = {4, 8, 16, 32, 64};
+
 // picks the instantiation for (sketch width, n, score source, projection)
-static hipError_t dispatch(const FusedArgs& a, int col_blocks, bool small, int source, bool proj) {
-    if (!proj) return small ? by_source<2, 32, false>(a, source) : by_source<2, 64, false>(a, source);
-    if (col_blocks == 1) return small ? by_source<2, 32, true>(a, source) : by_source<2, 64, true>(a, source);
-    return small ? by_source<4, 32, true>(a, source) : by_source<4, 64, true>(a, source);
+static hipError_t dispatch(const FusedArgs& a, int col_blocks, int kpt, int source, bool proj) {
+    if (!proj) return by_keys<2, false>(a, kpt, source);
+    if (col_blocks == 1) return by_keys<2, true>(a, kpt, source);
+    return by_keys<4, true>(a, kpt, source);
 }
 
 hipError_t configure_fused(curdkv_ctx* ctx) {
@@ -166,8 +186,8 @@ hipError_t configure_fused(curdkv_ctx* ctx) {
     if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return hipSuccess;
     FusedArgs a{};
     a.dyn = dyn;
-    for (int small = 0; small < 2; ++small) {
-        const hipError_t e = dispatch(a, ctx->col_blocks, small != 0, ctx->cfg.score_source, !ctx->cfg.no_projection);
+    for (int kpt : kKeyVariants) {
+        const hipError_t e = dispatch(a, ctx->col_blocks, kpt, ctx->cfg.score_source, !ctx->cfg.no_projection);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -193,8 +213,7 @@ hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
                         void* V_out, hipStream_t stream) {
     FusedArgs a{ctx, K, V, (int32_t)n, n_sink, d_offsets, scores, indices, K_out, V_out, stream, -1};
-    return dispatch(a, ctx->col_blocks, n <= 32 * kFusedThreads, ctx->cfg.score_source,
-                    !ctx->cfg.no_projection);
+    return dispatch(a, ctx->col_blocks, keys_per_thread(n), ctx->cfg.score_source, !ctx->cfg.no_projection);
 }
 
 }  // namespace curdkv
