@@ -319,6 +319,7 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     if (fusable && !big_gather)
         return launch_fused(ctx, K, V, n, n_sink, ctx->plan.d_offsets, scores, indices, K_out, V_out, st) == hipSuccess
                    ? CURDKV_OK : CURDKV_ERR_HIP;
+    const bool scores_wanted = scores != nullptr;
     if (!scores) {
         if (!ctx->d_scores_ws &&
             hipMalloc((void**)&ctx->d_scores_ws, (size_t)ctx->heads * (size_t)ctx->cfg.max_tokens * sizeof(float)) != hipSuccess) {
@@ -339,7 +340,7 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     // back), which saves the separate pass over the scores
     int bph = 0;
     if (launch_scores(ctx, K, V, n, scores, st, /*normalise=*/false, &bph) != hipSuccess) return CURDKV_ERR_HIP;
-    if (launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st, bph) != hipSuccess) return CURDKV_ERR_HIP;
+    if (launch_select(ctx, scores, n, n_sink, ctx->plan.d_offsets, indices, st, bph, scores_wanted) != hipSuccess) return CURDKV_ERR_HIP;
     if (total == 0) return CURDKV_OK;
     return launch_compact(ctx, K, V, n, indices, ctx->plan.d_offsets, total, K_out, V_out, st) == hipSuccess
                ? CURDKV_OK : CURDKV_ERR_HIP;

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
                                                                     const int64_t* __restrict__ offsets,
                                                                     int32_t* __restrict__ indices,
                                                                     const float* __restrict__ partial,
-                                                                    int scale_blocks) {
+                                                                    int scale_blocks, int write_scaled) {
     __shared__ StreamShared sm;
     const int head = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
     const int64_t s = n_sink < n ? n_sink : n;
     const HeadScale scale = head_scale(partial + (size_t)head * kMaxBlocksPerHead, scale_blocks, n);
     auto scale_all = [&]() {                       // heads that need no selection still get normalised
-        if (scale.on)
+        if (scale.on && write_scaled)
             for (int64_t j = tid; j < n; j += kSelThreads) sc[j] = scale(sc[j]);
     };
 
@@ -110,9 +110,10 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
     }
     const int64_t chunks = (n + kStreamChunk - 1) / kStreamChunk;
 
-    // one chunk of scores, thread-strided.  With on-the-fly normalisation the first
-    // pass scales and writes back; a thread always re-reads its own tokens, so later
-    // passes see the scaled values without any fence.
+    // one chunk of scores, thread-strided.  With on-the-fly normalisation the first pass
+    // scales and writes back; a thread always re-reads its own tokens, so later passes see
+    // the scaled values without any fence.  When nobody wants the normalised scores
+    // (write_scaled = 0) nothing is written and every pass scales what it loads.
     bool scaling_pass = scale.on;
     auto load_chunk = [&](float (&v)[kStreamU], int64_t chunk) {
 #pragma unroll
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
             for (int u = 0; u < kStreamU; ++u) {
                 const int64_t j = chunk * kStreamChunk + u * kSelThreads + tid;
                 v[u] = scale(v[u]);
-                if (j < n) sc[j] = v[u];
+                if (write_scaled && j < n) sc[j] = v[u];
             }
         }
     };
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kSelThreads) void select_stream_kernel(float* __res
     if (tid == 0) sm.list_count = 0;
     __syncthreads();
     for_each_key([&](uint32_t key, int64_t, int) { atomicAdd(&sm.hist[key >> 20], 1u); });
-    scaling_pass = false;
+    scaling_pass = scale.on && !write_scaled;      // written back: the later passes read scaled values
     __syncthreads();
     find_bin_from_top(sm, kStreamBins, (uint32_t)m);
     const uint32_t d1 = sm.digit;
@@ -299,14 +300,14 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(float* __restri
                                                                  const int64_t* __restrict__ offsets,
                                                                  int32_t* __restrict__ indices, int32_t cap,
                                                                  const float* __restrict__ partial,
-                                                                 int scale_blocks) {
+                                                                 int scale_blocks, int write_scaled) {
     extern __shared__ int32_t stage[];             // [cap]
     __shared__ SelectShared<kSelThreads, KPT> sm;
     const int head = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t o0 = offsets[head];
     const int32_t k = (int32_t)(offsets[head + 1] - o0);
-    if (k <= 0 && scale_blocks <= 0) return;
+    if (k <= 0 && (scale_blocks <= 0 || !write_scaled)) return;
     int32_t* out = indices + o0;
     float* sc = scores + (size_t)head * n;
     const int32_t s = n_sink < n ? n_sink : n;
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(float* __restri
         for (int it = 0; it < KPT; ++it) {
             v[it] = scale(v[it]);
             const int32_t j = it * kSelThreads + tid;
-            if (scale.on && j < n) sc[j] = v[it];
+            if (scale.on && write_scaled && j < n) sc[j] = v[it];
             x[it] = order_key(v[it]);
         }
     }
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(kSelThreads) void select_reg_kernel(float* __restri
 template <int KPT>
 static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, int32_t n_sink,
                              const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
-                             int scale_blocks) {
+                             int scale_blocks, int write_scaled) {
     // the staging area takes what the kernel's static LDS leaves, within the dynamic size the
     // kernel was configured for (configure_select); indices beyond it go straight to memory
     const size_t fixed = sizeof(SelectShared<kSelThreads, KPT>) + 256;
@@ -347,7 +348,7 @@ static hipError_t launch_reg(const curdkv_ctx* ctx, float* scores, int32_t n, in
     if (cap > n) cap = n;
     if (cap < 0) cap = 0;
     select_reg_kernel<KPT><<<dim3((unsigned)ctx->heads), kSelThreads, (size_t)cap * 4, stream>>>(
-        scores, n, n_sink, d_offsets, indices, (int32_t)cap, ctx->d_partial, scale_blocks);
+        scores, n, n_sink, d_offsets, indices, (int32_t)cap, ctx->d_partial, scale_blocks, write_scaled);
     return hipGetLastError();
 }
 
@@ -368,15 +369,16 @@ hipError_t configure_select(curdkv_ctx* ctx) {
 
 hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_t n_sink,
                          const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
-                         int scale_blocks) {
+                         int scale_blocks, bool write_scaled) {
     const int32_t n32 = (int32_t)n;
-    if (n <= 4 * kSelThreads) return launch_reg<4>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
-    if (n <= 8 * kSelThreads) return launch_reg<8>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
-    if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
-    if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
-    if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks);
+    const int ws = write_scaled ? 1 : 0;
+    if (n <= 4 * kSelThreads) return launch_reg<4>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks, ws);
+    if (n <= 8 * kSelThreads) return launch_reg<8>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks, ws);
+    if (n <= 16 * kSelThreads) return launch_reg<16>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks, ws);
+    if (n <= 32 * kSelThreads) return launch_reg<32>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks, ws);
+    if (n <= 36 * kSelThreads) return launch_reg<36>(ctx, scores, n32, n_sink, d_offsets, indices, stream, scale_blocks, ws);
     select_stream_kernel<<<dim3((unsigned)ctx->heads), kSelThreads, 0, stream>>>(
-        scores, n, n_sink, d_offsets, indices, ctx->d_partial, scale_blocks);
+        scores, n, n_sink, d_offsets, indices, ctx->d_partial, scale_blocks, ws);
     return hipGetLastError();
 }
 

@@ -196,7 +196,8 @@ def test_one_call_without_scores_and_fallback_paths(gu):
                 wl.CONFIGS["c1"]):
         gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True, fused=False)
     # scores = NULL on both paths: indices and rows must equal the run that returned scores
-    for cfg in (wl.scaled(wl.CONFIGS["c3"], n=1000), wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=1000)):
+    for cfg in (wl.scaled(wl.CONFIGS["c3"], n=1000), wl.scaled(wl.CONFIGS["c2"], kv_heads=4, n=1000),
+                wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=2, n=40000, dirichlet_total_frac=None)):
         K, V = wl.host_cache(cfg)
         Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
         b = wl.budgets_for(cfg, 0.2); off = wl.offsets_for(b); tot = int(off[-1])
