@@ -168,9 +168,21 @@ __global__ __launch_bounds__(256) void normalise_kernel(float* __restrict__ scor
     const float inv = zero ? 0.f : (float)(1.0 / tot);
     const float uniform = (float)(1.0 / (double)n);
     float* sh = scores + (size_t)head * n;
-    for (int64_t j = (int64_t)chunk * blockDim.x + threadIdx.x; j < n;
-         j += (int64_t)chunks_per_head * blockDim.x)
-        sh[j] = zero ? uniform : sh[j] * inv;
+    constexpr int kInFlight = 8;                   // loads issued before the first store
+    const int64_t stride = (int64_t)chunks_per_head * blockDim.x;
+    for (int64_t j0 = (int64_t)chunk * blockDim.x + threadIdx.x; j0 < n; j0 += kInFlight * stride) {
+        float v[kInFlight];
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int64_t j = j0 + u * stride;
+            v[u] = j < n ? sh[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int64_t j = j0 + u * stride;
+            if (j < n) sh[j] = zero ? uniform : v[u] * inv;
+        }
+    }
 }
 
 // GQA fold: mean over the query heads of a group.  The sum is taken in double,
