@@ -129,3 +129,27 @@ def test_million_token_heads(gu):
     budgets = np.array([50_000, 333_334], dtype=np.int32)
     worst, _ = gu.run_and_check(cfg, budgets, one_call=True, fused=False)
     assert worst < 1e-4
+
+
+def test_c3_full_results_do_not_depend_on_scheduling(gu):
+    # every sum is taken in a fixed order, so two runs on the same cache agree bit for bit,
+    # on both paths, whatever order the workgroups ran in
+    import torch
+    cfg = wl.CONFIGS["c3"]
+    L, H, n = cfg.layers, cfg.kv_heads, cfg.n
+    Kd, Vd = wl.device_cache(cfg)
+    budgets = wl.budgets_for(cfg, 0.10)
+    with B.Context(L, H, cfg.group, cfg.d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
+        for one_call in (True, False):
+            first = None
+            for rep in range(3):
+                sc, idx, Ko, Vo, _ = gu.run_path(ctx, Kd, Vd, n, budgets, cfg.n_sink, cfg.dtype, one_call)
+                got = (sc.view(torch.int32).clone(), idx.clone(), Ko.view(torch.int16).clone(), Vo.view(torch.int16).clone())
+                if first is None:
+                    first = got
+                else:
+                    for a, b in zip(first, got):
+                        assert torch.equal(a, b), (one_call, rep)
+                del sc, idx, Ko, Vo
+    del Kd, Vd
+    torch.cuda.empty_cache()
