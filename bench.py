@@ -141,7 +141,7 @@ def main():
     ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed, args.source,
                     not args.no_projection)
     s = cfg.n_sink
-    fused = ctx.uses_fused_kernel(n) and total * 5 <= heads * n * 2
+    fused = ctx.uses_fused_kernel(n) and total * 4 <= heads * n
 
     def step_calls(ev=None):
         if ev:

@@ -311,11 +311,11 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     const int rc = sync_offsets(ctx, offsets, budgets, n, st, &total);
     if (rc != CURDKV_OK) return rc;
     if (total > 0 && (!indices || !K_out || !V_out)) return CURDKV_ERR_INVALID_ARG;
-    // One kernel for everything when it applies -- unless more than ~40 % of the rows are
+    // One kernel for everything when it applies -- unless more than a quarter of the rows are
     // kept: the gather then dominates and the stand-alone gather kernel (four times the
     // threads per CU) moves rows a little faster than the fused kernel's last phase.
     const bool fusable = fused_applicable(ctx, n);
-    const bool big_gather = total * 5 > (int64_t)ctx->heads * n * 2;
+    const bool big_gather = total * 4 > (int64_t)ctx->heads * n;
     if (fusable && !big_gather)
         return launch_fused(ctx, K, V, n, n_sink, ctx->plan.d_offsets, scores, indices, K_out, V_out, st) == hipSuccess
                    ? CURDKV_OK : CURDKV_ERR_HIP;
