@@ -43,6 +43,28 @@ def _normalise_by_max():
     orc.normalise = normalise
 
 
+def _normalise_by_sum_of_squares():
+    def normalise(lkv):
+        t = float(np.sqrt(np.sum(lkv * lkv)))
+        return lkv / t if t > 0 else np.full(lkv.shape[0], 1.0 / lkv.shape[0])
+    orc.normalise = normalise
+
+
+def _select_sinks_from_the_end():
+    orig = _orig["select"]
+    def select(lt, k, s):
+        lt = np.asarray(lt, dtype=np.float64)
+        n = lt.shape[0]
+        if not (0 <= k <= n) or s < 0:
+            raise ValueError("bad budget")
+        if k <= s:
+            return np.arange(k, dtype=np.int64)
+        recent = np.arange(n - s, n, dtype=np.int64)             # the last s tokens instead of the first
+        top = np.argsort(-lt[: n - s], kind="stable")[: k - s].astype(np.int64)
+        return np.sort(np.concatenate([top, recent]))
+    orc.select = select
+
+
 def _normalise_zero_stays_zero():
     def normalise(lkv):
         total = float(np.sum(lkv))
@@ -199,13 +221,13 @@ def _adaptive_with(**kw):
             g = min(floor, n - sp)
         else:
             g = min(max(floor - sp, 0), n - sp)
-        R = H * (k - sp) - H * g
+        R = H * (k - sp) - (0 if kw.get("open_budget_ignores_safeguard") else H * g)
         cand = lt[:, sp:]
         order = np.argsort(-cand, axis=1, kind="stable")
         rank = np.empty_like(order)
         rows = np.arange(H)[:, None]
         rank[rows, order] = np.arange(n - sp)[None, :]
-        open_ = rank >= g
+        open_ = rank >= (0 if kw.get("safe_tokens_compete_again") else g)
         head_of = np.broadcast_to(rows, cand.shape)[open_]
         vals = cand[open_]
         if kw.get("ties_last_head_first"):
@@ -213,7 +235,7 @@ def _adaptive_with(**kw):
         else:
             picked = np.argsort(-vals, kind="stable")[:max(R, 0)]
         extra = np.bincount(head_of[picked], minlength=H)
-        return (sp + g + extra).astype(np.int64)
+        return ((0 if kw.get("sinks_not_counted") else sp) + g + extra).astype(np.int64)
     orc.adaptive_budgets = adaptive_budgets
 
 
@@ -295,6 +317,11 @@ MUTANTS = {
     "adaptive_sinks_outside_safeguard": lambda: _adaptive_with(sinks_outside_safeguard=True),
     "adaptive_ties_last_head_first": lambda: _adaptive_with(ties_last_head_first=True),
     "adaptive_uniform": _adaptive_uniform,
+    "adaptive_open_budget_ignores_safeguard": lambda: _adaptive_with(open_budget_ignores_safeguard=True),
+    "adaptive_safe_tokens_compete_again": lambda: _adaptive_with(safe_tokens_compete_again=True),
+    "adaptive_sinks_not_counted": lambda: _adaptive_with(sinks_not_counted=True),
+    "normalise_by_sum_of_squares": _normalise_by_sum_of_squares,
+    "select_sinks_from_the_end": _select_sinks_from_the_end,
     "scores_ignore_source": _scores_ignore_source,
     "scores_project_without_sketch": _scores_project_even_when_told_not_to,
     "eviction_rows_misaligned": lambda: _eviction("no_scaling_loss"),
