@@ -239,6 +239,37 @@ def _adaptive_with(**kw):
     orc.adaptive_budgets = adaptive_budgets
 
 
+def _cut_with(**kw):
+    """adaptive_cut_score with one mistake in how the cut is read off the layer-wide ranking."""
+    def adaptive_cut_score(lt, k, s, alpha):
+        lt = np.asarray(lt, dtype=np.float64)
+        H, n = lt.shape
+        sp = min(s, n)
+        if k <= sp:
+            return None
+        g = min(max(int(np.floor(alpha * k)) - sp, 0), n - sp)
+        R = H * (k - sp) - H * g
+        if R <= 0:
+            return None
+        cand = lt[:, sp:]
+        order = np.argsort(-cand, axis=1, kind="stable")
+        rank = np.empty_like(order)
+        rows = np.arange(H)[:, None]
+        rank[rows, order] = np.arange(n - sp)[None, :]
+        open_ = rank >= g
+        if kw.get("before_safeguard_mask"):            # safe tokens take part in the ranking
+            vals = cand.reshape(-1)
+        else:
+            vals = cand[open_]
+        ranked = np.sort(vals)[::-1]
+        if kw.get("largest_admitted"):
+            return float(ranked[0])
+        if kw.get("first_left_out"):
+            return float(ranked[min(R, ranked.size - 1)])
+        return float(ranked[R - 1])
+    orc.adaptive_cut_score = adaptive_cut_score
+
+
 def _adaptive_uniform():
     orc.adaptive_budgets = lambda lt, k, s, alpha: np.full(np.asarray(lt).shape[0], k, dtype=np.int64)
 
@@ -320,6 +351,9 @@ MUTANTS = {
     "adaptive_open_budget_ignores_safeguard": lambda: _adaptive_with(open_budget_ignores_safeguard=True),
     "adaptive_safe_tokens_compete_again": lambda: _adaptive_with(safe_tokens_compete_again=True),
     "adaptive_sinks_not_counted": lambda: _adaptive_with(sinks_not_counted=True),
+    "cut_score_is_largest_admitted": lambda: _cut_with(largest_admitted=True),
+    "cut_score_is_first_left_out": lambda: _cut_with(first_left_out=True),
+    "cut_score_ranked_before_safeguard_mask": lambda: _cut_with(before_safeguard_mask=True),
     "normalise_by_sum_of_squares": _normalise_by_sum_of_squares,
     "select_sinks_from_the_end": _select_sinks_from_the_end,
     "scores_ignore_source": _scores_ignore_source,
