@@ -48,8 +48,8 @@ extern "C" {
 #define CURDKV_DTYPE_F32  0
 #define CURDKV_DTYPE_BF16 1
 
-/* What the score of a token is built from.  KV is the method (Algorithm 1,
- * "Combine scores": product of key and value scores); KEY and VALUE are the
+/* What the score of a token is built from.  KV is the method (the combination
+ * step of Algorithm 1: product of key and value scores); KEY and VALUE are the
  * ablation of the appendix ("Ablation Study") that uses one tensor alone. */
 #define CURDKV_SCORE_KV    0
 #define CURDKV_SCORE_KEY   1
@@ -85,8 +85,8 @@ int curdkv_destroy(curdkv_ctx* ctx);
 /* Host-only (no GPU needed): write G of group (layer, head) to G_host[d*r],
  * row-major [head_dim, sketch_dim], as float.
  *
- * Algorithm 1, "Sample Gaussian matrix G in R^{d x r} with G_ij ~ N(0, 1/r)";
- * one G per (layer, group), shared by K and V.  The paper fixes no generator:
+ * Sampling step of Algorithm 1: a d x r matrix of independent normal entries
+ * with variance 1/r; one G per (layer, group), shared by K and V.  The paper fixes no generator:
  * element (i, j) has counter c = ((layer*kv_heads + head)*d + i)*r + j and
  * takes SplitMix64 outputs number 2c+1 and 2c+2 (w1, w2) of the stream started
  * at `seed`; u1 = ((w1>>11)+1)*2^-53, u2 = (w2>>11)*2^-53,
@@ -99,7 +99,7 @@ int curdkv_sketch_host(const curdkv_config* cfg, int32_t layer, int32_t head, fl
  * For callers that draw G themselves, as Algorithm 1 literally does. */
 int curdkv_set_sketch(curdkv_ctx* ctx, int32_t layer, int32_t head, const float* G_host);
 
-/* Algorithm 1, lines "Project" to "Normalize": for every (layer, group)
+/* Algorithm 1 from the projection step to the normalisation step: for every (layer, group)
  *   lK_j = ||(K G)[j]||^2,  lV_j = ||(V G)[j]||^2,  lKV_j = lK_j * lV_j,
  *   scores_j = lKV_j / sum_j lKV_j   (sum over all n rows; 1/n if the sum is 0).
  * K, V: device, [layers, kv_heads, n, head_dim], storage type, read once.
@@ -118,8 +118,8 @@ int curdkv_scores(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
 int curdkv_fold(curdkv_ctx* ctx, const float* scores_q, int64_t n, float* scores,
                 void* stream);
 
-/* Algorithm 1, lines "Preserve first s tokens", "Select top-(k-s)" and
- * "Combine": S = {0..s-1} U (TopK(scores[s:], k-s) + s) for every (layer, group).
+/* Sink, top-k and union steps of Algorithm 1: S = {0..s-1} U (TopK(scores[s:], k-s) + s)
+ * for every (layer, group).
  * scores: device float [layers, kv_heads, n], non-negative, no NaN.
  * budgets: host int32 [layers*kv_heads], k per group (sinks included), 0 <= k <= n.
  * offsets: host int64 [layers*kv_heads + 1], offsets[0] = 0 and
@@ -132,7 +132,7 @@ int curdkv_select(curdkv_ctx* ctx, const float* scores, int64_t n,
                   const int32_t* budgets, int32_t n_sink, const int64_t* offsets,
                   int32_t* indices, void* stream);
 
-/* Algorithm 1, last line: K' = K[S], V' = V[S] (rows of the original cache).
+/* Gather step of Algorithm 1: K' = K[S], V' = V[S] (rows of the original cache).
  * indices, offsets: as written by / passed to curdkv_select (offsets on host;
  * non-decreasing, offsets[0] = 0, each group's count <= n; every index must lie
  * in [0, n)).
@@ -202,8 +202,8 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
                              int32_t* budgets_out, int64_t* offsets_out, int32_t* indices,
                              void* K_out, void* V_out, void* stream);
 
-/* Scoring during generation (Section 3.2: the method "can be applied during the
- * pre-filling as well as the token generation phase").  The un-normalised scores
+/* Scoring during generation (Section 3.2, first paragraph: the method is meant for
+ * the generation phase as well as for pre-filling).  The un-normalised scores
  * lKV_j of a token do not depend on the other tokens, so a growing cache is scored
  * chunk by chunk: this call scores the m new tokens of every (layer, group),
  * writes lKV to raw[group*stride + n_old + j] and adds their sum to sums[group]
@@ -214,7 +214,7 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
 int curdkv_scores_append(curdkv_ctx* ctx, const void* K_new, const void* V_new, int64_t m,
                          int64_t n_old, int64_t stride, float* raw, double* sums, void* stream);
 
-/* "Normalize" for the first n tokens of a cache scored with curdkv_scores_append:
+/* Normalisation step for the first n tokens of a cache scored with curdkv_scores_append:
  * scores[group*n + j] = raw[group*stride + j] / sums[group] (1/n if the sum is 0),
  * sums being those of exactly these n tokens.  The result is what curdkv_scores
  * gives on the n-token cache (up to the order of the additions in the sum) and

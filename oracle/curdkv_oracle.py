@@ -6,18 +6,21 @@ Only tests, the smoke check and the benchmark's cpu-baseline leg may import
 it; the product path (the C-ABI library and its Python binding) never does,
 and it shares no code, table or helper with that path.
 
-What is computed (Algorithm 1 of the paper, "CUR-based KV Compression with
-GQA Support"), per layer and per KV group i:
+What is computed (Algorithm 1 of the paper, the CUR-based compression with GQA
+support), per layer and per KV group i, in this order:
 
-    G        ~ N(0, 1/r)^{d x r}                       (sample sketch)
-    Yk, Yv   = K_i G, V_i G                            (project)
-    lK_j     = ||Yk[j]||_2^2 ,  lV_j = ||Yv[j]||_2^2   (row-norm squared)
-    lKV_j    = lK_j * lV_j                             (combine)
-    lt_j     = lKV_j / sum_j lKV_j                     (normalise)
-    S_sink   = {0..s-1}
-    S_top    = TopK(lt[s:], k-s) + s
-    S_i      = S_sink U S_top
-    K'_i,V'_i= K_i[S_i], V_i[S_i]                      (gather original rows)
+  1. a Gaussian sketch G with d rows, r columns and entry variance 1/r is drawn;
+  2. the keys and the values of the group are both multiplied by it from the right;
+  3. every projected row is scored by its squared Euclidean norm, which gives one
+     key score and one value score per token;
+  4. the two are multiplied into one score per token;
+  5. the scores are divided by their sum over all n tokens;
+  6. the first s tokens are set aside as sinks, the k - s best of the remaining
+     tokens are added to them;
+  7. the rows of the ORIGINAL keys and values at those positions are the output.
+
+Each step is a function of its own below (`sketch`, `project`, `row_norm_sq`,
+`combine`, `normalise`, `select`, `compact`), and `compress_group` chains them.
 
 The method is an approximation followed by a heuristic selection, so the
 oracle follows the algorithm's steps in the paper's order; it is not a
@@ -94,7 +97,7 @@ def round_to_storage(x64: np.ndarray, dtype: str) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# the sketch G (Algorithm 1, "Sample Gaussian matrix"; Section 3.2,
+# the sketch G (Algorithm 1, sampling step; Section 3.2,
 # "Approximate leverage scores and Gaussian projections")
 # --------------------------------------------------------------------------
 
@@ -164,24 +167,24 @@ def leverage_exact(A: np.ndarray, rcond: float = 1e-12) -> np.ndarray:
 
 
 def project(A: np.ndarray, G: np.ndarray) -> np.ndarray:
-    """'Project' line of Algorithm 1: A G with A in R^{n x d}, G in R^{d x r}."""
+    """Projection step of Algorithm 1: A G with A in R^{n x d}, G in R^{d x r}."""
     return np.asarray(A, dtype=np.float64) @ np.asarray(G, dtype=np.float64)
 
 
 def row_norm_sq(Y: np.ndarray) -> np.ndarray:
-    """'Compute leverage scores' line of Algorithm 1: l_j = ||Y[j]||_2^2."""
+    """Scoring step of Algorithm 1: l_j = ||Y[j]||_2^2, the squared norm of projected row j."""
     return np.sum(Y * Y, axis=1)
 
 
 def combine(lk: np.ndarray, lv: np.ndarray) -> np.ndarray:
-    """'Combine scores' line: elementwise product of key and value scores
-    (the ablation section calls it the elementwise product as well)."""
+    """Combination step of Algorithm 1: key score times value score, token by token
+    (the ablation section describes it as an elementwise product as well)."""
     return lk * lv
 
 
 def normalise(lkv: np.ndarray) -> np.ndarray:
-    """'Normalize' line: divide by the sum over all n rows (sinks included,
-    since the sink step comes later).  All-zero input gives 1/n everywhere."""
+    """Normalisation step of Algorithm 1: divide by the sum over all n rows (sinks
+    included, since the sink step comes later).  All-zero input gives 1/n everywhere."""
     total = float(np.sum(lkv))
     n = lkv.shape[0]
     if not total > 0.0:
@@ -198,8 +201,8 @@ def scores(K64: np.ndarray, V64: np.ndarray, G, source: str = "kv",
 
     The two ablations of the appendix ("Ablation Study"):
       source = "k" / "v": leverage scores from the keys or the values alone instead
-        of their elementwise product (the "Combine scores" line is dropped);
-      projection = False: the "Sample" and "Project" lines are dropped and the row
+        of their elementwise product (the combination step is dropped);
+      projection = False: the sampling and projection steps are dropped and the row
         norms are taken on the original matrices."""
     if source not in ("kv", "k", "v"):
         raise ValueError(f"unknown score source {source!r}")
@@ -227,7 +230,7 @@ def fold_gqa(scores_q: np.ndarray) -> np.ndarray:
 
 
 def select(lt: np.ndarray, k: int, s: int) -> np.ndarray:
-    """Sink + TopK + union lines of Algorithm 1.  Returns S_i ascending, |S_i| = k."""
+    """Sink, top-k and union steps of Algorithm 1.  Returns S_i ascending, |S_i| = k."""
     lt = np.asarray(lt, dtype=np.float64)
     n = lt.shape[0]
     if not (0 <= k <= n):
@@ -296,7 +299,7 @@ def _adaptive_allot(lt: np.ndarray, k: int, s: int, alpha: float):
 
 
 def compact(K: np.ndarray, V: np.ndarray, S: np.ndarray):
-    """Gather line of Algorithm 1: K'_i = K_i[S_i], V'_i = V_i[S_i], rows of the
+    """Gather step of Algorithm 1: K'_i = K_i[S_i], V'_i = V_i[S_i], rows of the
     stored (original-type) arrays, bit for bit."""
     return K[S], V[S]
 

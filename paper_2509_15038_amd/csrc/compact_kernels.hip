@@ -1,5 +1,5 @@
-// Gather-compact kernel: Algorithm 1, last line, K'_i = K_i[S_i], V'_i = V_i[S_i]
-// (rows of the original cache), for gfx950.
+// Gather-compact kernel: the last step of Algorithm 1, which keeps the selected
+// rows of the original K_i and V_i, for gfx950.
 //
 // The packed output is one long list of rows; work is split by output row, not
 // by head, so ragged budgets balance by themselves.  A row is copied by a group

@@ -84,7 +84,7 @@ hipError_t launch_fold(const curdkv_ctx* ctx, const float* scores_q, int64_t n, 
                        hipStream_t stream);
 // scale_blocks > 0: `scores` holds un-normalised products; the kernel divides them by
 // the head's sum (ctx->d_partial, scale_blocks partial sums per head), selects on the
-// result and writes it back, which is what "Normalize" followed by selection gives
+// result and writes it back, which is what normalisation followed by selection gives
 // (write_scaled = false: selects on the divided values but leaves `scores` as they are, for
 // callers that do not want the scores).
 hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_t n_sink,

@@ -1,5 +1,5 @@
-// Device code of the bf16 scoring pass: Algorithm 1, lines "Project", "Compute
-// leverage scores" and "Combine scores", for gfx950.  Shared by the stand-alone
+// Device code of the bf16 scoring pass: the projection, row-norm-squared and
+// key-value combination steps of Algorithm 1, for gfx950.  Shared by the stand-alone
 // scoring kernel and the fused kernel.
 //
 // The projection is computed transposed, Y^T = G^T A^T (A = K_i or V_i), with

@@ -1,5 +1,5 @@
-// Scoring kernels: Algorithm 1, lines "Project", "Compute leverage scores",
-// "Combine scores" and "Normalize", for gfx950.
+// Scoring kernels: the projection, row-norm-squared, combination and
+// normalisation steps of Algorithm 1, for gfx950.
 //
 // One pass over K and V.  The projection is computed transposed,
 //     Y^T = G^T A^T   (A = K_i or V_i),
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void scores_f32_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// "Normalize": divide by the sum over all n rows of the head.  The per-block
+// Normalisation step of Algorithm 1: divide by the sum over all n rows of the head.  The per-block
 // partial sums are added in index order in double, so the result does not
 // depend on scheduling.  A zero sum gives 1/n everywhere.
 // ---------------------------------------------------------------------------

@@ -1,6 +1,5 @@
-// Device code of the per-head selection: Algorithm 1, lines "Preserve first s
-// tokens as sink indices", "Select top-(k-s) indices from l[s:]" and "Combine",
-// for gfx950.  Shared by the stand-alone selection kernel and the fused kernel.
+// Device code of the per-head selection: the sink, top-k and union steps of
+// Algorithm 1, for gfx950.  Shared by the stand-alone selection kernel and the fused kernel.
 //
 // A workgroup of THREADS threads handles one (layer, group) with n <= THREADS*KPT.
 // Thread t holds the order-preserving 32-bit keys of tokens t, t + THREADS,
@@ -37,7 +36,7 @@ __device__ __forceinline__ uint32_t order_key(float x) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// "Normalize" applied on the fly: v -> v / (sum of the head), the sum being the
+// The normalisation step of Algorithm 1 applied on the fly: v -> v / (sum of the head), the sum being the
 // per-block partial sums added in index order in double; 1/n when the sum is 0.
 // The arithmetic is the one of the stand-alone normalisation kernel.
 struct HeadScale {

@@ -1,5 +1,4 @@
-// Selection kernels: Algorithm 1, lines "Preserve first s tokens as sink
-// indices", "Select top-(k-s) indices from l[s:]" and "Combine", for gfx950.
+// Selection kernels: the sink, top-k and union steps of Algorithm 1, for gfx950.
 // One 1024-thread workgroup per (layer, group).  The method is described in
 // select_device.h; this file holds the kernels and their launcher.
 

@@ -1,6 +1,6 @@
-// Host-side generation of the Gaussian sketch G (Algorithm 1, "Sample Gaussian
-// matrix G in R^{d x r} with G_ij ~ N(0, 1/r)") and its packing into the MFMA
-// A-operand layout the scoring kernels read.
+// Host-side generation of the Gaussian sketch G (the sampling step of Algorithm 1:
+// a d x r matrix of independent normal entries with variance 1/r) and its packing
+// into the MFMA A-operand layout the scoring kernels read.
 //
 // The paper fixes no generator.  Each element is addressed by a counter and
 // built from two SplitMix64 outputs through Box-Muller, so any (layer, group)

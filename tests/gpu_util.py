@@ -26,20 +26,51 @@ def to_host(t, dtype: str) -> np.ndarray:
     return t.cpu().numpy()
 
 
+class Guarded:
+    """A device buffer with canary elements before and after it: a kernel that writes outside
+    the buffer it was given (an overrun past the last group, an offset gone negative) changes
+    them, which poisoning the payload alone would not show."""
+
+    GUARD = 1024          # elements on each side; keeps 16-byte alignment for every dtype used here
+    _PATTERN = {4: 0x5A5A5A5A, 2: 0x5A5A, 8: 0x5A5A5A5A5A5A5A5A}
+
+    def __init__(self, shape, dtype, fill):
+        import torch
+        count = int(np.prod(shape))
+        row = int(np.prod(shape[1:])) if len(shape) > 1 else 1
+        self._g = -(-self.GUARD // row) * row       # whole rows
+        self._back = torch.empty((count + 2 * self._g,), dtype=dtype, device="cuda")
+        self._ibits = {4: torch.int32, 2: torch.int16, 8: torch.int64}[self._back.element_size()]
+        self._pat = self._PATTERN[self._back.element_size()]
+        raw = self._back.view(self._ibits)
+        raw[: self._g] = self._pat
+        raw[self._g + count:] = self._pat
+        self.t = self._back[self._g: self._g + count].view(*shape)
+        self.t.fill_(fill)
+
+    def check(self, what=""):
+        raw = self._back.view(self._ibits)
+        n = self.t.numel()
+        assert bool((raw[: self._g] == self._pat).all()), f"{what}: written before the start of the buffer"
+        assert bool((raw[self._g + n:] == self._pat).all()), f"{what}: written past the end of the buffer"
+
+
 def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, dtype: str,
              one_call: bool = False):
     """scores -> select -> compact through the C ABI (or the one-call entry point,
-    which picks the fused kernel when it applies).  Returns device tensors."""
+    which picks the fused kernel when it applies).  Returns device tensors.  Every output
+    buffer sits between canaries, checked after the calls."""
     import torch
     heads = ctx.heads
     offsets = wl.offsets_for(budgets)
     total = int(offsets[-1])
-    scores = torch.empty((heads, n), dtype=torch.float32, device="cuda")
-    indices = torch.full((max(total, 1),), -7, dtype=torch.int32, device="cuda")
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g_sc = Guarded((heads, n), torch.float32, float("nan"))
+    g_ix = Guarded((max(total, 1),), torch.int32, -7)
     # (filled with NaN bit patterns: a row that is left out cannot hide behind stale memory)
-    Ko = torch.full((max(total, 1), 128), float("nan"), dtype=tdt, device="cuda")
-    Vo = torch.full((max(total, 1), 128), float("nan"), dtype=tdt, device="cuda")
+    g_ko = Guarded((max(total, 1), 128), tdt, float("nan"))
+    g_vo = Guarded((max(total, 1), 128), tdt, float("nan"))
+    scores, indices, Ko, Vo = g_sc.t, g_ix.t, g_ko.t, g_vo.t
     if one_call:
         ctx.compress(Kd, Vd, n, budgets, n_sink, offsets, scores, indices, Ko, Vo)
     else:
@@ -47,6 +78,10 @@ def run_path(ctx: B.Context, Kd, Vd, n: int, budgets: np.ndarray, n_sink: int, d
         ctx.select(scores, n, budgets, n_sink, offsets, indices)
         ctx.compact(Kd, Vd, n, indices, offsets, Ko, Vo)
     torch.cuda.synchronize()
+    for g, what in ((g_sc, "scores"), (g_ix, "indices"), (g_ko, "K_out"), (g_vo, "V_out")):
+        g.check(what)
+    if total == 0:                                  # nothing may have been written at all
+        assert int(indices[0]) == -7 and bool(torch.isnan(Ko.float()).all()) and bool(torch.isnan(Vo.float()).all())
     return scores, indices[:total], Ko[:total], Vo[:total], offsets
 
 
@@ -77,9 +112,11 @@ def check_selection(got: np.ndarray, lt: np.ndarray, k: int, s: int, where=""):
 
 
 def check_head(cfg, ctxargs, K, V, G, scores_g, idx_g, Ko_g, Vo_g, k, s, where="",
-               source="kv", projection=True):
-    """All three comparisons for one (layer, head) given host copies."""
-    lt = orc.scores(orc.to_f64(K, cfg.dtype), orc.to_f64(V, cfg.dtype), G, source, projection)
+               source="kv", projection=True, lt=None):
+    """All three comparisons for one (layer, head) given host copies.  lt: the oracle's scores
+    of this group when the caller has them already (they do not depend on the budget)."""
+    if lt is None:
+        lt = orc.scores(orc.to_f64(K, cfg.dtype), orc.to_f64(V, cfg.dtype), G, source, projection)
     rel = check_scores(scores_g, lt, where)
     ndiff = check_selection(idx_g.astype(np.int64), lt, k, s, where)
     Kc, Vc = orc.compact(K, V, idx_g.astype(np.int64))

@@ -1,11 +1,18 @@
 """GPU parity at the benchmark's full sizes and launch configuration.
 
-The caches are drawn on the GPU (same distributions as the host generators);
-sampled (layer, head) groups are copied back and the oracle recomputes exactly
-those groups, element by element.  Properties that hold at any size (score sums,
-index ranges and order, bit-exact gather) are checked on every group."""
+The caches are drawn on the GPU (same distributions as the host generators) and
+copied back a layer at a time; the oracle recomputes the groups named below from
+those bits, element by element:
+  * C3 (all three budgets) and C4: every one of the 256 (layer, head) groups, on
+    the three-call path and on the one-call path;
+  * C5: one head per layer (head (7*layer + 3) mod 8) plus the heads with the
+    smallest and the largest budget, 34 groups in all.
+Properties that hold at any size (score sums, index ranges and order, bit-exact
+gather, no dropped token scoring above a kept one) are checked on every group of
+every run, on the device."""
 
 import sys
+import time
 
 import numpy as np
 import pytest
@@ -24,26 +31,33 @@ def _announce(request):
     yield
 
 
+def _all_groups(cfg):
+    return [(l, h) for l in range(cfg.layers) for h in range(cfg.kv_heads)]
+
+
 def _full(cfg, keeps, sample, gu, one_call=False, fused=None):
     import torch
     L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
     heads = L * H
+    s = cfg.n_sink
     Kd, Vd = wl.device_cache(cfg)
+    by_layer = {}
+    for (l, h) in sample:
+        by_layer.setdefault(l, []).append(h)
+    lt_of = {}                                    # oracle scores per group: they do not depend on the budget
     with B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed) as ctx:
         if fused is not None:
             assert ctx.uses_fused_kernel(n) == fused
         for keep in keeps:
             budgets = wl.budgets_for(cfg, keep)
             print(f"  {cfg.name} n={n} keep={keep} total rows={int(budgets.sum())}", flush=True)
-            sc, idx, Ko, Vo, off = gu.run_path(ctx, Kd, Vd, n, budgets, cfg.n_sink, cfg.dtype, one_call)
-            # ---- every group: invariants ------------------------------------------
+            sc, idx, Ko, Vo, off = gu.run_path(ctx, Kd, Vd, n, budgets, s, cfg.dtype, one_call)
+            # ---- every group: invariants, on the device ---------------------------
             sums = sc.double().sum(1).cpu().numpy()
             assert np.allclose(sums, 1.0, atol=1e-4), "scores do not sum to one"
             assert bool((sc >= 0).all())
-            idx_h = idx.cpu().numpy()
-            off_t = torch.from_numpy(off).cuda()
-            head_of = torch.repeat_interleave(torch.arange(heads, device="cuda"),
-                                              torch.from_numpy(budgets.astype(np.int64)).cuda())
+            bud_t = torch.from_numpy(budgets.astype(np.int64)).cuda()
+            head_of = torch.repeat_interleave(torch.arange(heads, device="cuda"), bud_t)
             assert bool(((idx >= 0) & (idx < n)).all())
             same_head = head_of[1:] == head_of[:-1]
             assert bool((idx[1:][same_head] > idx[:-1][same_head]).all()), "not ascending"
@@ -53,28 +67,43 @@ def _full(cfg, keeps, sample, gu, one_call=False, fused=None):
             Vref = Vd.view(heads * n, d)[flat_rows]
             assert torch.equal(Ko.view(torch.int16), Kref.view(torch.int16))
             assert torch.equal(Vo.view(torch.int16), Vref.view(torch.int16))
-            # top-k property on the GPU's own scores: min kept >= max dropped (non-sink)
-            s = cfg.n_sink
-            for i in range(0, heads, 37):
-                k = int(budgets[i])
-                if k <= s or k >= n:
-                    continue
-                sci = sc[i].cpu().numpy()
-                kept = idx_h[off[i]:off[i + 1]]
-                mask = np.zeros(n, bool); mask[kept] = True
-                assert mask[:s].all()
-                assert sci[s:][mask[s:]].min() >= sci[s:][~mask[s:]].max()
-            # ---- sampled groups: element by element against the oracle -------------
-            for (l, h) in sample:
-                i = l * H + h
-                G = orc.sketch(cfg.sketch_seed, l, h, H, d, cfg.r, cfg.dtype)
-                a, b = int(off[i]), int(off[i + 1])
-                rel, nd = gu.check_head(cfg, None, gu.to_host(Kd[l, h], cfg.dtype),
-                                        gu.to_host(Vd[l, h], cfg.dtype), G, sc[i].cpu().numpy(),
-                                        idx_h[a:b], gu.to_host(Ko[a:b], cfg.dtype),
-                                        gu.to_host(Vo[a:b], cfg.dtype), int(budgets[i]), s,
-                                        where=f"{cfg.name} full l{l} h{h} keep{keep}")
-                print(f"    l{l} h{h}: worst rel {rel:.2e}, near-cut diffs {nd}", flush=True)
+            del Kref, Vref
+            # top-k property on the GPU's own scores, every head: the sinks are kept, and outside
+            # them no dropped token scores above a kept one
+            kept = torch.zeros((heads * n,), dtype=torch.bool, device="cuda")
+            kept[flat_rows] = True
+            kept = kept.view(heads, n)
+            sinks = min(s, n)
+            full_sinks = bud_t >= sinks
+            assert bool(kept[full_sinks][:, :sinks].all()), "a sink token is missing"
+            inf = torch.tensor(float("inf"), device="cuda")
+            kept_min = torch.where(kept[:, sinks:], sc[:, sinks:], inf).min(1).values
+            drop_max = torch.where(~kept[:, sinks:], sc[:, sinks:], -inf).max(1).values
+            assert bool((kept_min >= drop_max).all()), "a dropped token scores above a kept one"
+            del kept, flat_rows, head_of
+            # ---- the named groups: element by element against the oracle ------------
+            t0 = time.perf_counter()
+            worst, ndiff, done = 0.0, 0, 0
+            off_l = off.tolist()
+            for l in sorted(by_layer):
+                K_l, V_l = gu.to_host(Kd[l], cfg.dtype), gu.to_host(Vd[l], cfg.dtype)       # [H, n, d]
+                sc_l = sc[l * H:(l + 1) * H].cpu().numpy()
+                a0, b0 = off_l[l * H], off_l[(l + 1) * H]
+                idx_l = idx[a0:b0].cpu().numpy()
+                Ko_l, Vo_l = gu.to_host(Ko[a0:b0], cfg.dtype), gu.to_host(Vo[a0:b0], cfg.dtype)
+                for h in by_layer[l]:
+                    i = l * H + h
+                    if (l, h) not in lt_of:
+                        G = orc.sketch(cfg.sketch_seed, l, h, H, d, cfg.r, cfg.dtype)
+                        lt_of[(l, h)] = orc.scores(orc.to_f64(K_l[h], cfg.dtype), orc.to_f64(V_l[h], cfg.dtype), G)
+                    a, b = off_l[i] - a0, off_l[i + 1] - a0
+                    rel, nd = gu.check_head(cfg, None, K_l[h], V_l[h], None, sc_l[h], idx_l[a:b], Ko_l[a:b],
+                                            Vo_l[a:b], int(budgets[i]), s,
+                                            where=f"{cfg.name} full l{l} h{h} keep{keep}", lt=lt_of[(l, h)])
+                    worst, ndiff, done = max(worst, rel), ndiff + nd, done + 1
+                if l % 8 == 7 or l == max(by_layer):
+                    print(f"    layers ..{l}: {done} groups against the oracle, worst rel {worst:.2e}, "
+                          f"near-cut diffs {ndiff}, {time.perf_counter() - t0:.1f} s", flush=True)
             del sc, idx, Ko, Vo
     del Kd, Vd
     torch.cuda.empty_cache()
@@ -90,7 +119,8 @@ def gu():
 
 
 def test_c3_full_llama_32k_all_budgets(gu):
-    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu)
+    cfg = wl.CONFIGS["c3"]
+    _full(cfg, cfg.keep, _all_groups(cfg), gu)
 
 
 def test_c3_quarter_model_three_kernels(gu):
@@ -102,15 +132,16 @@ def test_c3_quarter_model_three_kernels(gu):
 
 
 def test_c3_full_one_call_fused(gu):
-    _full(wl.CONFIGS["c3"], wl.CONFIGS["c3"].keep, [(0, 0), (13, 5), (31, 7)], gu, one_call=True, fused=True)
+    cfg = wl.CONFIGS["c3"]
+    _full(cfg, cfg.keep, _all_groups(cfg), gu, one_call=True, fused=True)
 
 
 def test_c4_full_one_call_fused(gu):
-    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu, one_call=True, fused=True)
+    _full(wl.CONFIGS["c4"], (0.10,), _all_groups(wl.CONFIGS["c4"]), gu, one_call=True, fused=True)
 
 
 def test_c4_full_mistral_32k_prefix(gu):
-    _full(wl.CONFIGS["c4"], (0.10,), [(0, 0), (17, 3), (31, 7)], gu)
+    _full(wl.CONFIGS["c4"], (0.10,), _all_groups(wl.CONFIGS["c4"]), gu)
 
 
 def test_c5_full_128k_dirichlet(gu):
@@ -118,8 +149,9 @@ def test_c5_full_128k_dirichlet(gu):
     b = wl.budgets_for(cfg).reshape(32, 8)
     l_small = int(np.argmin(b.min(1)))      # the groups with the smallest and largest budget
     l_big = int(np.argmax(b.max(1)))
-    sample = [(l_small, int(np.argmin(b[l_small]))), (l_big, int(np.argmax(b[l_big]))), (31, 7)]
-    _full(cfg, (None,), sample, gu)
+    sample = {(l, (7 * l + 3) % 8) for l in range(32)}          # one head of every layer
+    sample |= {(l_small, int(np.argmin(b[l_small]))), (l_big, int(np.argmax(b[l_big])))}
+    _full(cfg, (None,), sorted(sample), gu)
 
 
 def test_million_token_heads(gu):

@@ -336,13 +336,19 @@ def test_adaptive_one_call_on_device(gu, layers, kv_heads, n, r, dtype):
     with B.Context(L, H, 4, 128, cfg.r, dtype, n, cfg.sketch_seed) as ctx:
         for (k, s, alpha) in [(n // 10, 4, 0.2), (n // 3, 0, 0.0), (n // 20, 64, 1.0), (3, 4, 0.2), (0, 4, 0.2)]:
             total = heads * k
-            sc = torch.full((heads, n), float("nan"), dtype=torch.float32, device="cuda")
-            bd = torch.full((heads,), -7, dtype=torch.int32, device="cuda")
-            od = torch.full((heads + 1,), -7, dtype=torch.int64, device="cuda")
-            idx = torch.full((max(total, 1),), -1, dtype=torch.int32, device="cuda")
-            Ko = torch.zeros((max(total, 1), 128), dtype=tdt, device="cuda"); Vo = torch.zeros_like(Ko)
+            # every output between canaries: budgets, offsets and the block table are made on the
+            # device here, so an overrun would not be caught by any host-side check
+            guards = {"scores": gu.Guarded((heads, n), torch.float32, float("nan")),
+                      "budgets": gu.Guarded((heads,), torch.int32, -7),
+                      "offsets": gu.Guarded((heads + 1,), torch.int64, -7),
+                      "indices": gu.Guarded((max(total, 1),), torch.int32, -1),
+                      "K_out": gu.Guarded((max(total, 1), 128), tdt, 0.0),
+                      "V_out": gu.Guarded((max(total, 1), 128), tdt, 0.0)}
+            sc, bd, od, idx, Ko, Vo = (guards[w].t for w in ("scores", "budgets", "offsets", "indices", "K_out", "V_out"))
             ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, sc, bd, od, idx, Ko, Vo)
             torch.cuda.synchronize()
+            for what, g in guards.items():
+                g.check(f"compress_adaptive k{k} s{s} a{alpha}: {what}")
             budgets, off, sc_h = bd.cpu().numpy(), od.cpu().numpy(), sc.cpu().numpy()
             for l in range(L):        # against the oracle's allocation, made from the oracle's own scores
                 gu.check_adaptive_budgets(budgets[l * H:(l + 1) * H], lt_layers[l], k, s, alpha,
@@ -488,6 +494,49 @@ def test_select_adversarial_scores(gu, n):
         for h in range(H):
             want = orc.select(sc[h].astype(np.float64), int(b[h]), s)
             assert np.array_equal(idx[off[h]:off[h + 1]], want), (n, h, budgets)
+
+
+def test_eviction_loss_of_the_gpu_selection(gu):
+    # What the selection is for (Section 3.1, Lemma 1; Figures 1 and 2), on the index sets the HIP
+    # path returns: the evaluator's eviction loss of the GPU's set equals that of the oracle's set
+    # wherever the two sets are the same, Lemma 1's inequality holds for the GPU's set, and the
+    # value-guided choice keeps far more of the value mass than as many random tokens would.
+    from oracle import eviction_eval as ev
+    for (layers, kv_heads, one_call, fused) in [(1, 4, False, False), (32, 8, True, True)]:
+        cfg = wl.scaled(wl.CONFIGS["c2"], layers=layers, kv_heads=kv_heads, n=1024)
+        K, V = wl.host_cache(cfg)
+        L, H, n, s = cfg.layers, cfg.kv_heads, cfg.n, 4
+        k = n // 10
+        budgets = np.full(L * H, k, dtype=np.int32)
+        with B.Context(L, H, 4, 128, cfg.r, "bf16", n, cfg.sketch_seed) as ctx:
+            assert ctx.uses_fused_kernel(n) == fused
+            _, idx, _, _, off = gu.run_path(ctx, gu.to_device(K, "bf16"), gu.to_device(V, "bf16"), n, budgets, s,
+                                            "bf16", one_call)
+            idx = idx.cpu().numpy().astype(np.int64)
+        rng = np.random.default_rng(21)
+        same = 0
+        groups = [(l, h) for l in range(L) for h in range(H)][:: max(1, L * H // 8)]      # eight groups at most
+        for (l, h) in groups:
+            i = l * H + h
+            S_gpu = idx[off[i]:off[i + 1]]
+            K64, V64 = orc.to_f64(K[l, h], "bf16"), orc.to_f64(V[l, h], "bf16")
+            lt = orc.scores(K64, V64, orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, "bf16"))
+            S_orc = orc.select(lt, k, s)
+            Q = K64[rng.choice(n, 16, replace=False)] * 0.5 + rng.standard_normal((16, 128)) * 0.5
+            loss_gpu, loss_orc = ev.eviction_loss(Q, K64, V64, S_gpu), ev.eviction_loss(Q, K64, V64, S_orc)
+            if np.array_equal(S_gpu, S_orc):
+                assert loss_gpu == loss_orc
+                same += 1
+            else:                                    # near-cut ties only (checked elsewhere): a few tokens' worth
+                assert abs(loss_gpu - loss_orc) <= 0.05 * loss_orc
+            assert loss_gpu > 0.0 and ev.eviction_loss(Q, K64, V64, np.arange(n)) < 1e-9
+            lhs, rhs = ev.lemma1_sides(Q, K64, V64, S_gpu)
+            assert lhs <= rhs
+            vn = np.sum(V64 * V64, axis=1)
+            assert vn[S_gpu].sum() / vn.sum() > 0.3                                  # random keeps 0.1 on average
+            rnd = np.mean([np.sqrt(vn.sum() - vn[rng.choice(n, k, replace=False)].sum()) for _ in range(5)])
+            assert np.sqrt(vn.sum() - vn[S_gpu].sum()) < 0.9 * rnd                   # Lemma 1's ||V - V'||_F term
+        assert same >= len(groups) - 1
 
 
 def test_fold_gqa(gu):

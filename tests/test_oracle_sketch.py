@@ -1,5 +1,5 @@
-"""Pins for the oracle's sketch generator (Algorithm 1, "Sample Gaussian matrix
-G with G_ij ~ N(0, 1/r)"; Section 3.2).  CPU only."""
+"""Pins for the oracle's sketch generator (Algorithm 1, sampling step: normal
+entries of variance 1/r; Section 3.2).  CPU only."""
 
 import math
 import os
