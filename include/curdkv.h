@@ -44,6 +44,7 @@ extern "C" {
 #define CURDKV_ERR_UNSUPPORTED -2   /* head_dim, sketch_dim or dtype the kernels do not cover */
 #define CURDKV_ERR_HIP         -3   /* a HIP runtime call failed (no device, launch error, ...) */
 #define CURDKV_ERR_OOM         -4   /* device or host allocation failed */
+#define CURDKV_ERR_TOO_LARGE   -5   /* more (layer, group) pairs than a non-allocating call's fixed workspace holds */
 
 #define CURDKV_DTYPE_F32  0
 #define CURDKV_DTYPE_BF16 1
@@ -182,6 +183,20 @@ int curdkv_uses_fused_kernel(const curdkv_ctx* ctx, int64_t n);
  * 0 <= budget <= n, 0 <= alpha <= 1. */
 int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
                             int32_t n_sink, double alpha, int32_t* budgets_out, void* stream);
+
+/* curdkv_adaptive_budgets for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results, same kernels; the histograms and per-layer state
+ * that curdkv_adaptive_budgets keeps in a buffer it allocates on first use live
+ * here in a static device array of the library (16 MiB + 12 KiB per GPU, resident
+ * from the moment the library is loaded, its address looked up at curdkv_create).
+ * The call makes no hipMalloc, hipFree or other allocating call.
+ * Limit: layers*kv_heads <= 1024, else CURDKV_ERR_TOO_LARGE and nothing is launched.
+ * All calls on one GPU, from every context, share the one array: two such calls
+ * that overlap in time on that GPU race; calls on one stream, or otherwise
+ * ordered, are safe (nothing in the array has to survive between calls). */
+int curdkv_adaptive_budgets_noalloc(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
+                                    int32_t n_sink, double alpha, int32_t* budgets_out, void* stream);
 
 /* AdaCurDKV in one call with nothing passing through the host (Algorithm 1 with the
  * head-wise budgets of Section 3.2, "Adaptive budget allocation"): scores as in

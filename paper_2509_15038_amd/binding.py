@@ -17,13 +17,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcurdkv.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_OOM = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_OOM, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5
 DTYPE_F32, DTYPE_BF16 = 0, 1
 _DTYPES = {"fp32": DTYPE_F32, "bf16": DTYPE_BF16}
 
 EXPORTS = ["curdkv_create", "curdkv_destroy", "curdkv_sketch_host", "curdkv_set_sketch",
            "curdkv_uses_fused_kernel", "curdkv_scores", "curdkv_fold", "curdkv_select", "curdkv_compact", "curdkv_compress",
-           "curdkv_adaptive_budgets", "curdkv_compress_adaptive", "curdkv_scores_append", "curdkv_normalise", "curdkv_strerror"]
+           "curdkv_adaptive_budgets", "curdkv_adaptive_budgets_noalloc", "curdkv_compress_adaptive", "curdkv_scores_append", "curdkv_normalise", "curdkv_strerror"]
 
 
 class CurdkvConfig(C.Structure):
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
     L.curdkv_compact.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp]
     L.curdkv_compress.argtypes = [vp, vp, vp, i64, vp, i32, vp, vp, vp, vp, vp, vp]
     L.curdkv_adaptive_budgets.argtypes = [vp, vp, i64, i32, i32, C.c_double, vp, vp]
+    L.curdkv_adaptive_budgets_noalloc.argtypes = [vp, vp, i64, i32, i32, C.c_double, vp, vp]
     L.curdkv_compress_adaptive.argtypes = [vp, vp, vp, i64, i32, i32, C.c_double, vp, vp, vp, vp, vp, vp, vp]
     L.curdkv_scores_append.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.curdkv_normalise.argtypes = [vp, vp, vp, i64, i64, vp, vp]
@@ -208,6 +209,13 @@ class Context:
                                            float(alpha), _ptr(budgets_out), _stream(stream))
         if rc != OK:
             raise CurdkvError(rc, "curdkv_adaptive_budgets")
+
+    def adaptive_budgets_noalloc(self, scores, n: int, budget: int, n_sink: int, alpha: float, budgets_out,
+                                 stream=None):
+        rc = lib().curdkv_adaptive_budgets_noalloc(self._h, _ptr(scores), int(n), int(budget), int(n_sink),
+                                                   float(alpha), _ptr(budgets_out), _stream(stream))
+        if rc != OK:
+            raise CurdkvError(rc, "curdkv_adaptive_budgets_noalloc")
 
     def compress_adaptive(self, K, V, n: int, budget: int, n_sink: int, alpha: float, scores,
                           budgets_out, offsets_out, indices, K_out, V_out, stream=None):

@@ -20,6 +20,8 @@
 //     budgets.
 // No token order is needed anywhere.
 
+#include <mutex>
+
 #include "select_device.h"
 
 namespace curdkv {
@@ -329,12 +331,52 @@ hipError_t configure_adaptive(curdkv_ctx* ctx) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, dyn);
 }
 
-size_t adaptive_workspace_bytes(const curdkv_ctx* ctx) {
-    return (size_t)ctx->heads * kAdaMaxBins * 4 + (size_t)ctx->heads * 4 +
-           (size_t)ctx->cfg.layers * sizeof(AdaLayerState);
+// Workspace of the allocation for `heads` (layer, group) pairs in `layers` layers: the per-head
+// histograms, the per-head counts above the decided prefix, the per-layer prefix.
+static constexpr size_t workspace_bytes_for(size_t heads, size_t layers) {
+    return heads * kAdaMaxBins * 4 + heads * 4 + layers * sizeof(AdaLayerState);
 }
 
-hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t k,
+size_t adaptive_workspace_bytes(const curdkv_ctx* ctx) {
+    return workspace_bytes_for((size_t)ctx->heads, (size_t)ctx->cfg.layers);
+}
+
+// ---- the same workspace as a static device array, for callers that cannot allocate ----------
+// curdkv_adaptive_budgets_noalloc runs the kernels above on this array instead of a buffer
+// from hipMalloc.  Every GPU the library is used on holds its own copy, at its own address,
+// from the moment the code object is loaded until the process ends.  On the host the array's
+// name is only a handle for hipGetSymbolAddress: the address the kernels are given is the one
+// that call returns, looked up once per device at curdkv_create.
+constexpr int kScratchMaxHeads = 1024;                 // layers * kv_heads the static workspace covers
+constexpr size_t kScratchBytes = workspace_bytes_for(kScratchMaxHeads, kScratchMaxHeads);   // 16 MiB + 12 KiB
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kScratchMaxDevices = 64;
+static void* g_scratch_ptr[kScratchMaxDevices];        // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+int adaptive_static_max_heads() { return kScratchMaxHeads; }
+
+// Called with `device` current.  Looks the array's device address up on first use.
+hipError_t adaptive_static_workspace_init(int device) {
+    if (device < 0 || device >= kScratchMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return hipSuccess;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+    return hipSuccess;
+}
+
+void* adaptive_static_workspace(int device) {
+    if (device < 0 || device >= kScratchMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[device];
+}
+
+hipError_t launch_adaptive(const curdkv_ctx* ctx, void* workspace, const float* scores, int64_t n, int32_t k,
                            int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream) {
     const int H = ctx->cfg.kv_heads, L = ctx->cfg.layers;
     if (k <= sp || R <= 0) {           // nothing to allot: k each, or all covered by the safeguard
@@ -342,7 +384,7 @@ hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n
         ada_uniform_kernel<<<dim3((unsigned)((ctx->heads + 255) / 256)), 256, 0, stream>>>(budgets, ctx->heads, v);
         return hipGetLastError();
     }
-    uint32_t* ws_hist = reinterpret_cast<uint32_t*>(ctx->d_adaptive_ws);
+    uint32_t* ws_hist = reinterpret_cast<uint32_t*>(workspace);
     uint32_t* ws_above = ws_hist + (size_t)ctx->heads * kAdaMaxBins;
     AdaLayerState* state = reinterpret_cast<AdaLayerState*>(ws_above + ctx->heads);
     const int bits = level_bits(H);

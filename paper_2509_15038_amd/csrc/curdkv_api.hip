@@ -135,6 +135,7 @@ const char* curdkv_strerror(int code) {
         case CURDKV_ERR_UNSUPPORTED: return "unsupported head_dim, sketch_dim, dtype or size";
         case CURDKV_ERR_HIP: return "HIP runtime error";
         case CURDKV_ERR_OOM: return "out of memory";
+        case CURDKV_ERR_TOO_LARGE: return "size beyond the fixed workspace of a call that does not allocate";
         default: return "unknown error code";
     }
 }
@@ -168,6 +169,9 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
     }
     ctx->lds_limit = lds;
     ctx->num_cu = cus > 0 ? cus : 256;
+    // address of the static workspace on this device (curdkv_adaptive_budgets_noalloc); a
+    // device number beyond the table only makes that one entry point unavailable
+    if (adaptive_static_workspace_init(ctx->device) != hipSuccess) (void)hipGetLastError();
 
     const size_t g_bytes = (size_t)ctx->heads * ctx->g_elems_per_head * storage_bytes(cfg->dtype);
     const size_t off_bytes = ((size_t)(ctx->heads + 1) * sizeof(int64_t) + 15) & ~(size_t)15;
@@ -364,7 +368,27 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
         ctx->d_adaptive_ws = nullptr;
         return CURDKV_ERR_OOM;
     }
-    return launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
+    return launch_adaptive(ctx, ctx->d_adaptive_ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
+                           (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
+}
+
+int curdkv_adaptive_budgets_noalloc(curdkv_ctx* ctx, const float* scores, int64_t n, int32_t budget,
+                                    int32_t n_sink, double alpha, int32_t* budgets_out, void* stream) {
+    if (!ctx || !scores || !budgets_out) return CURDKV_ERR_INVALID_ARG;
+    if (!on_own_device(ctx)) return CURDKV_ERR_INVALID_ARG;
+    if (n < 1 || n > ctx->cfg.max_tokens || n_sink < 0 || budget < 0 || budget > n) return CURDKV_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return CURDKV_ERR_INVALID_ARG;
+    if (ctx->cfg.kv_heads > 1024) return CURDKV_ERR_UNSUPPORTED;
+    if (ctx->heads > adaptive_static_max_heads()) return CURDKV_ERR_TOO_LARGE;   // beyond the static workspace
+    void* ws = adaptive_static_workspace(ctx->device);      // looked up at curdkv_create; nothing is allocated here
+    if (!ws) return CURDKV_ERR_HIP;
+    const int64_t sp = n_sink < n ? n_sink : n;
+    int64_t g = (int64_t)std::floor(alpha * (double)budget) - sp;
+    if (g < 0) g = 0;
+    if (g > n - sp) g = n - sp;
+    const long long H = ctx->cfg.kv_heads;
+    const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
+    return launch_adaptive(ctx, ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }
 
@@ -411,7 +435,7 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
     if (g > n - sp) g = n - sp;
     const long long H = ctx->cfg.kv_heads;
     const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
-    if (launch_adaptive(ctx, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out, st) != hipSuccess ||
+    if (launch_adaptive(ctx, ctx->d_adaptive_ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out, st) != hipSuccess ||
         launch_adaptive_plan(ctx, budgets_out, n, total, offsets_out, ctx->d_adaptive_blocks, st) != hipSuccess)
         return CURDKV_ERR_HIP;
     if (total == 0) return CURDKV_OK;

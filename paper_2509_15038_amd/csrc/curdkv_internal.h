@@ -99,8 +99,16 @@ hipError_t configure_select(curdkv_ctx* ctx);
 hipError_t configure_fused(curdkv_ctx* ctx);
 hipError_t configure_adaptive(curdkv_ctx* ctx);
 size_t adaptive_workspace_bytes(const curdkv_ctx* ctx);
-hipError_t launch_adaptive(const curdkv_ctx* ctx, const float* scores, int64_t n, int32_t k,
+// workspace: adaptive_workspace_bytes(ctx) bytes of device memory; nothing in it has to be
+// cleared beforehand, and its contents mean nothing after the call.
+hipError_t launch_adaptive(const curdkv_ctx* ctx, void* workspace, const float* scores, int64_t n, int32_t k,
                            int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream);
+// The static device array that serves as that workspace for curdkv_adaptive_budgets_noalloc:
+// its address on `device` (looked up by adaptive_static_workspace_init, which curdkv_create
+// calls with the device current), and the number of (layer, group) pairs it is sized for.
+hipError_t adaptive_static_workspace_init(int device);
+void* adaptive_static_workspace(int device);
+int adaptive_static_max_heads();
 // offsets[i] = budgets[0] + .. + budgets[i-1], kept within [0, total] (offsets[heads] = total), and
 // the gather block table for them; everything on the device.
 hipError_t launch_adaptive_plan(const curdkv_ctx* ctx, const int32_t* budgets, int64_t n, int64_t total,
