@@ -188,7 +188,7 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, same results, same kernels; the histograms and per-layer state
  * that curdkv_adaptive_budgets keeps in a buffer it allocates on first use live
- * here in a static device array of the library (16 MiB + 12 KiB per GPU, resident
+ * here in a static device array of the library (24 MiB + 32 KiB per GPU, resident
  * from the moment the library is loaded, its address looked up at curdkv_create).
  * The call makes no hipMalloc, hipFree or other allocating call.
  * Limit: layers*kv_heads <= 1024, else CURDKV_ERR_TOO_LARGE and nothing is launched.

@@ -424,9 +424,12 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
         ctx->d_adaptive_blocks = nullptr;
         return CURDKV_ERR_OOM;
     }
-    // normalised scores first: the allocation compares them across the heads of a layer
-    const hipError_t e = fused_applicable(ctx, n)
-        ? launch_fused(ctx, K, V, n, 0, ctx->d_zero_offsets, scores, nullptr, nullptr, nullptr, st)
+    // normalised scores first: the allocation compares them across the heads of a layer.  The
+    // fused kernel, where it applies, also leaves every head's key histogram in the workspace.
+    const bool fused = fused_applicable(ctx, n);
+    const hipError_t e = fused
+        ? launch_fused(ctx, K, V, n, n_sink, ctx->d_zero_offsets, scores, nullptr, nullptr, nullptr, st,
+                       adaptive_hist_buffer(ctx, ctx->d_adaptive_ws), adaptive_layer_state(ctx, ctx->d_adaptive_ws))
         : launch_scores(ctx, K, V, n, scores, st);
     if (e != hipSuccess) return CURDKV_ERR_HIP;
     const int64_t sp = n_sink < n ? n_sink : n;
@@ -435,11 +438,16 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
     if (g > n - sp) g = n - sp;
     const long long H = ctx->cfg.kv_heads;
     const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
-    if (launch_adaptive(ctx, ctx->d_adaptive_ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out, st) != hipSuccess ||
-        launch_adaptive_plan(ctx, budgets_out, n, total, offsets_out, ctx->d_adaptive_blocks, st) != hipSuccess)
+    bool planned = false;
+    if (launch_adaptive(ctx, ctx->d_adaptive_ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out, st,
+                        fused, offsets_out, ctx->d_adaptive_blocks, &planned) != hipSuccess)
+        return CURDKV_ERR_HIP;
+    if (!planned && launch_adaptive_plan(ctx, budgets_out, n, total, offsets_out, ctx->d_adaptive_blocks, st) != hipSuccess)
         return CURDKV_ERR_HIP;
     if (total == 0) return CURDKV_OK;
-    if (launch_select(ctx, scores, n, n_sink, offsets_out, indices, st) != hipSuccess ||
+    // (`planned`: budgets were allotted layer-wide, and the allocation has left every head's threshold)
+    if (launch_select(ctx, scores, n, n_sink, offsets_out, indices, st, 0, true,
+                      planned ? adaptive_thresholds(ctx, ctx->d_adaptive_ws) : nullptr) != hipSuccess ||
         launch_compact(ctx, K, V, n, indices, offsets_out, total, K_out, V_out, st, ctx->d_adaptive_blocks) != hipSuccess)
         return CURDKV_ERR_HIP;
     return CURDKV_OK;

@@ -23,6 +23,13 @@ struct BlockInfo {                     // for gather block b, whose first output
     int32_t pad;
 };
 
+// Per-layer state of the head-wise budget allocation (adaptive_kernels.hip), in its workspace.
+struct AdaLayerState {
+    uint32_t done;                     // workgroups of the layer that have handed in their keys
+    uint32_t overflow;                 // some head's cut bin was too full for its segment
+    uint32_t pad[2];
+};
+
 // Device copy of the offsets, refreshed when they change, followed by the
 // per-gather-block table.
 struct Plan {
@@ -87,9 +94,12 @@ hipError_t launch_fold(const curdkv_ctx* ctx, const float* scores_q, int64_t n, 
 // result and writes it back, which is what normalisation followed by selection gives
 // (write_scaled = false: selects on the divided values but leaves `scores` as they are, for
 // callers that do not want the scores).
+// known_thresholds (device, one {key, need} pair per head as the budget allocation leaves them,
+// adaptive_thresholds): heads whose entry is valid skip the search for their threshold.
 hipError_t launch_select(const curdkv_ctx* ctx, float* scores, int64_t n, int32_t n_sink,
                          const int64_t* d_offsets, int32_t* indices, hipStream_t stream,
-                         int scale_blocks = 0, bool write_scaled = true);
+                         int scale_blocks = 0, bool write_scaled = true,
+                         const void* known_thresholds = nullptr);
 hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
                           const int32_t* indices, const int64_t* d_offsets, int64_t total,
                           void* K_out, void* V_out, hipStream_t stream,
@@ -101,8 +111,22 @@ hipError_t configure_adaptive(curdkv_ctx* ctx);
 size_t adaptive_workspace_bytes(const curdkv_ctx* ctx);
 // workspace: adaptive_workspace_bytes(ctx) bytes of device memory; nothing in it has to be
 // cleared beforehand, and its contents mean nothing after the call.
+// hist_ready: the per-head histograms (adaptive_hist_buffer) have been written, and the layers'
+// state (adaptive_layer_state) reset, by a kernel launched earlier on the stream (launch_fused
+// with hist_out); otherwise a kernel of this call makes them from `scores`.
+// offsets, block_info (device) given: where budgets are allotted layer-wide, the same launch
+// also writes the budgets' prefix sums (every layer keeps kv_heads*k rows) and the gather's
+// block table, and *planned is set; where every head gets the same budget they are left to
+// launch_adaptive_plan and *planned stays false.
 hipError_t launch_adaptive(const curdkv_ctx* ctx, void* workspace, const float* scores, int64_t n, int32_t k,
-                           int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream);
+                           int32_t sp, int32_t g, long long R, int32_t* budgets, hipStream_t stream,
+                           bool hist_ready = false, int64_t* offsets = nullptr, BlockInfo* block_info = nullptr,
+                           bool* planned = nullptr);
+uint32_t* adaptive_hist_buffer(const curdkv_ctx* ctx, void* workspace);
+// per head {threshold key, ties to keep} after launch_adaptive has allotted budgets layer-wide
+// (key 0xFFFFFFFF where a head's budget comes from its safeguard, not from the layer's threshold)
+const void* adaptive_thresholds(const curdkv_ctx* ctx, void* workspace);
+AdaLayerState* adaptive_layer_state(const curdkv_ctx* ctx, void* workspace);
 // The static device array that serves as that workspace for curdkv_adaptive_budgets_noalloc:
 // its address on `device` (looked up by adaptive_static_workspace_init, which curdkv_create
 // calls with the device current), and the number of (layer, group) pairs it is sized for.
@@ -114,8 +138,12 @@ int adaptive_static_max_heads();
 hipError_t launch_adaptive_plan(const curdkv_ctx* ctx, const int32_t* budgets, int64_t n, int64_t total,
                                 int64_t* offsets, BlockInfo* block_info, hipStream_t stream);
 bool fused_applicable(const curdkv_ctx* ctx, int64_t n);
+// hist_out (device, [heads][4096]) given: the kernel also writes every head's histogram of the
+// candidates' keys (tokens n_sink and up) over the 4096 bins of the selection (select_device.h)
+// and resets layer_state, for the head-wise budget allocation that follows it.
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
-                        void* V_out, hipStream_t stream);
+                        void* V_out, hipStream_t stream, uint32_t* hist_out = nullptr,
+                        AdaLayerState* layer_state = nullptr);
 
 }  // namespace curdkv

@@ -30,7 +30,8 @@ template <int CB, int KPT, int SRC, bool PROJ>
 __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     const uint4* __restrict__ K, const uint4* __restrict__ V, const uint4* __restrict__ Gp,
     int32_t n, int32_t n_sink, const int64_t* __restrict__ offsets, float* __restrict__ scores_out,
-    int32_t* __restrict__ indices, u32x4* __restrict__ K_out, u32x4* __restrict__ V_out) {
+    int32_t* __restrict__ indices, u32x4* __restrict__ K_out, u32x4* __restrict__ V_out,
+    uint32_t* __restrict__ hist_out, AdaLayerState* __restrict__ layer_state, int heads_per_layer) {
     extern __shared__ float sc[];                  // [n rounded up to 64]; later int32 stage[n]
     __shared__ SelectShared<kFusedThreads, KPT> sm;
     __shared__ float wsum[kFusedWaves];
@@ -76,6 +77,18 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
         }
         x[it] = order_key(v);
     }
+    const int32_t s = n_sink < n ? n_sink : n;
+    if (hist_out) {
+        // for the head-wise budget allocation: the bin12 histogram of this head's candidates,
+        // made here because the keys are in registers anyway
+        build_hist12<kFusedThreads, KPT>(x, n, s, sm);
+        uint32_t* dst = hist_out + (size_t)head * kBins12;
+        for (int i = tid; i < kBins12; i += kFusedThreads) dst[i] = sm.hist[i];
+        if (tid == 0 && head % heads_per_layer == 0) {       // a fresh count of finished workgroups for the layer
+            layer_state[head / heads_per_layer].done = 0;
+            layer_state[head / heads_per_layer].overflow = 0;
+        }
+    }
     const int64_t o0 = offsets[head];
     const int32_t k = (int32_t)(offsets[head + 1] - o0);
     if (k <= 0) return;
@@ -84,7 +97,6 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     // ---- 4. selection ------------------------------------------------------------------
     int32_t* stage = reinterpret_cast<int32_t*>(sc);
     int32_t* out = indices + o0;
-    const int32_t s = n_sink < n ? n_sink : n;
     select_core<kFusedThreads, KPT>(x, n, s, k, sm, stage, n, out);
     for (int32_t p = tid; p < k; p += kFusedThreads) out[p] = stage[p];
 
@@ -128,6 +140,8 @@ struct FusedArgs {
     float* scores;
     int32_t* indices;
     void *K_out, *V_out;
+    uint32_t* hist_out;
+    AdaLayerState* layer_state;
     hipStream_t stream;
     int dyn;                 // >= 0: only raise the kernel's dynamic LDS limit to this, no launch
 };
@@ -140,7 +154,8 @@ static hipError_t one(const FusedArgs& a) {
     const size_t lds = (((size_t)a.n + 63) & ~(size_t)63) * 4;
     fused_kernel<CB, KPT, SRC, PROJ><<<dim3((unsigned)a.ctx->heads), kFusedThreads, lds, a.stream>>>(
         (const uint4*)a.K, (const uint4*)a.V, (const uint4*)a.ctx->d_G, a.n, a.n_sink, a.d_offsets,
-        a.scores, a.indices, (u32x4*)a.K_out, (u32x4*)a.V_out);
+        a.scores, a.indices, (u32x4*)a.K_out, (u32x4*)a.V_out, a.hist_out, a.layer_state,
+        a.ctx->cfg.kv_heads);
     return hipGetLastError();
 }
 
@@ -181,7 +196,7 @@ static hipError_t dispatch(const FusedArgs& a, int col_blocks, int kpt, int sour
 }
 
 hipError_t configure_fused(curdkv_ctx* ctx) {
-    const int dyn = ctx->lds_limit - 24 * 1024;      // what the kernels' static LDS leaves
+    const int dyn = ctx->lds_limit - 28 * 1024;      // what the kernels' static LDS leaves
     if (dyn <= 48 * 1024) return hipSuccess;
     if (ctx->cfg.dtype != CURDKV_DTYPE_BF16 || ctx->col_blocks > 2) return hipSuccess;
     FusedArgs a{};
@@ -211,8 +226,9 @@ bool fused_applicable(const curdkv_ctx* ctx, int64_t n) {
 
 hipError_t launch_fused(const curdkv_ctx* ctx, const void* K, const void* V, int64_t n, int32_t n_sink,
                         const int64_t* d_offsets, float* scores, int32_t* indices, void* K_out,
-                        void* V_out, hipStream_t stream) {
-    FusedArgs a{ctx, K, V, (int32_t)n, n_sink, d_offsets, scores, indices, K_out, V_out, stream, -1};
+                        void* V_out, hipStream_t stream, uint32_t* hist_out, AdaLayerState* layer_state) {
+    if (!layer_state) hist_out = nullptr;          // the two go together
+    FusedArgs a{ctx, K, V, (int32_t)n, n_sink, d_offsets, scores, indices, K_out, V_out, hist_out, layer_state, stream, -1};
     return dispatch(a, ctx->col_blocks, keys_per_thread(n), ctx->cfg.score_source, !ctx->cfg.no_projection);
 }
 

@@ -278,6 +278,34 @@ def test_adaptive_budgets_ties_across_heads(gu):
         _ada_case(gu, sc, k, s, alpha)
 
 
+@pytest.mark.parametrize("H,n", [(512, 70), (1024, 41), (100, 300)])
+def test_adaptive_budgets_many_heads(gu, H, n):
+    # far more KV heads per layer than any GQA model has: the per-head digit histograms of the
+    # allocation's last step then take fewer bits per level (the header allows up to 1024 heads)
+    rng = np.random.default_rng([H, n, 5])
+    sc = rng.lognormal(0.0, 1.5, size=(2, H, n)).astype(np.float32)
+    sc /= sc.sum(-1, keepdims=True)
+    sc[1, :, : n // 2] = np.round(sc[1, :, : n // 2] * 64) / 64 + np.float32(1e-3)   # ties across heads
+    for (k, s, alpha) in [(n // 4, 4, 0.2), (n // 2, 0, 0.0), (n - 1, 2, 0.5)]:
+        _ada_case(gu, sc, k, s, alpha)
+
+
+def test_adaptive_budgets_general_routes(gu):
+    # inputs that the usual route of the allocation hands to its general one: a layer whose
+    # scores are (nearly) all equal, so that the bin holding the threshold is too full for
+    # the key lists; scores of 2 and above, which all share the last bin; and both at once
+    rng = np.random.default_rng(77)
+    H, n = 8, 6000
+    sc = np.empty((4, H, n), dtype=np.float32)
+    sc[0] = 1.0 / n                                                                # all equal
+    sc[1] = (1.0 + rng.integers(0, 4, size=(H, n)) * 2.0 ** -23).astype(np.float32) / n   # last-bit ties, one bin
+    sc[2] = rng.lognormal(3.0, 1.0, size=(H, n)).astype(np.float32) + 2.0        # everything >= 2
+    sc[3] = rng.lognormal(0.0, 3.0, size=(H, n)).astype(np.float32)              # straddles 2
+    sc[3, 2] = 5.0
+    for (k, s, alpha) in [(n // 10, 4, 0.2), (n // 3, 0, 0.0), (n - 5, 4, 0.3)]:
+        _ada_case(gu, sc, k, s, alpha)
+
+
 def test_adaptive_end_to_end_c3_shape(gu):
     # scores -> adaptive budgets -> select -> compact, the selection being the layer-wide one
     import torch
