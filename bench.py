@@ -261,6 +261,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None,
                     help="number of layers (default: the config's 32): fewer layers are the slice of the cache "
                          "one GPU holds when the model's KV heads are spread over several")
+    ap.add_argument("--tokens", type=int, default=None, help="tokens per head (default: the config's)")
+    ap.add_argument("--sketch-dim", type=int, default=None, help="sketch width r (default: the config's)")
     ap.add_argument("--source", default="kv", choices=["kv", "k", "v"],
                     help="ablation: score from keys and values (the method), keys only, values only")
     ap.add_argument("--no-projection", action="store_true", help="ablation: no Gaussian projection")
@@ -290,6 +292,10 @@ def main():
     cfg = wl.CONFIGS[args.config]
     if args.layers is not None:
         cfg = wl.scaled(cfg, layers=args.layers)
+    if args.tokens is not None:
+        cfg = wl.scaled(cfg, n=args.tokens)
+    if args.sketch_dim is not None:
+        cfg = wl.scaled(cfg, r=args.sketch_dim)
     keep = cfg.keep[0] if args.keep is None else args.keep
     budgets = wl.budgets_for(cfg, keep)
     total = int(budgets.astype(np.int64).sum())
@@ -297,7 +303,7 @@ def main():
     heads = L * H
     plain = args.source == "kv" and not args.no_projection
     extras = (plain and not args.headline_only and args.config == "c3" and args.keep is None
-              and args.layers is None)
+              and args.layers is None and args.tokens is None and args.sketch_dim is None)
 
     Kd, Vd = wl.device_cache(cfg)
     rows_max = max(total, int(heads * n * 0.5) if extras else 0, 1)

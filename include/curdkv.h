@@ -25,7 +25,16 @@
  *   - Capturing a compute call in a HIP graph: run the same call (same offsets,
  *     same optional buffers) once and synchronise before the capture, so that
  *     the capture neither uploads offsets nor allocates scratch; both would
- *     make the call unfit for capture.
+ *     make the call unfit for capture.  The captured kernels read the offsets
+ *     and the gather's block table from the context's single device copy: as
+ *     long as the graph may be replayed, call curdkv_select / curdkv_compact /
+ *     curdkv_compress on that context with these same offsets only (or give the
+ *     graph a context of its own).  A graph replayed after the copy has changed
+ *     would run the captured grid against the new offsets: its results would be
+ *     meaningless and, where the new offsets reach further than the captured
+ *     buffers, its writes out of bounds: such a graph must not be replayed.
+ *     curdkv_compress_adaptive keeps offsets and table in caller buffers and has
+ *     no such constraint.
  *   - K and V are row-major [layers, kv_heads, n, head_dim] in the context's
  *     storage type; token j of group (l, h) starts at element
  *     ((l*kv_heads + h)*n + j)*head_dim.  Base pointers must be 16-byte aligned.

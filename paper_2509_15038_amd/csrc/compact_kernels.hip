@@ -21,7 +21,7 @@ template <int ROW_U4>
 __global__ __launch_bounds__(256) void compact_kernel(
     const u32x4* __restrict__ K, const u32x4* __restrict__ V, int64_t n,
     const int32_t* __restrict__ indices, const int64_t* __restrict__ offsets,
-    const BlockInfo* __restrict__ block_info, int64_t total,
+    const BlockInfo* __restrict__ block_info, int64_t total, int heads,
     u32x4* __restrict__ K_out, u32x4* __restrict__ V_out) {
     constexpr int kRowsPerIter = 256 / ROW_U4;
     constexpr int kIters = 4;                                   // rows in flight per thread
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void compact_kernel(
     const int rsub = threadIdx.x / ROW_U4;
     const int64_t p0 = (int64_t)blockIdx.x * kCompactRowsPerBlock;
     const BlockInfo bi = block_info[blockIdx.x];
-    int h = bi.head;                                            // head of row p0
+    int h = bi.head < heads ? (bi.head < 0 ? 0 : bi.head) : heads - 1;   // head of row p0
     int64_t head_end = bi.head_end;                             // offsets[h + 1]
 
     for (int pass = 0; pass < kPasses; ++pass) {
@@ -47,7 +47,10 @@ __global__ __launch_bounds__(256) void compact_kernel(
 #pragma unroll
         for (int it = 0; it < kIters; ++it) {
             const int64_t p = p0 + (pass * kIters + it) * kRowsPerIter + rsub;
-            while (head_end <= p && p < total) head_end = offsets[++h + 1];   // rows ascend: h only moves forward
+            // rows ascend: h only moves forward (and never past the last head, whatever the table
+            // and the offsets hold: a graph replayed after the context's offsets have changed
+            // must not walk off the cache)
+            while (head_end <= p && p < total && h + 1 < heads) head_end = offsets[++h + 1];
             ok[it] = p < total && idx[it] >= 0 && idx[it] < n;  // never read outside the cache
             const size_t row = ((size_t)h * n + (ok[it] ? idx[it] : 0)) * ROW_U4 + c;
             src_k[it] = K + row;
@@ -78,11 +81,11 @@ hipError_t launch_compact(const curdkv_ctx* ctx, const void* K, const void* V, i
     const int64_t blocks = (total + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
     if (ctx->cfg.dtype == CURDKV_DTYPE_BF16) {
         compact_kernel<16><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total,
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total, ctx->heads,
             (u32x4*)K_out, (u32x4*)V_out);
     } else {
         compact_kernel<32><<<dim3((unsigned)blocks), 256, 0, stream>>>(
-            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total,
+            (const u32x4*)K, (const u32x4*)V, n, indices, d_offsets, block_info, total, ctx->heads,
             (u32x4*)K_out, (u32x4*)V_out);
     }
     return hipGetLastError();

@@ -206,12 +206,16 @@ __global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
 // are paid per workgroup) and write its scores once, at its end, so the lower bound is what
 // makes a wave's share fit its LDS stage.  Above that, the smallest count is taken that fills
 // the rounds in which the workgroups pass through the chip to within 3 % of the best
-// (measured at n = 32768: 2 per head for 256 heads, 4 for 128 and 384, 7-8 for 288).
+// (measured at n = 32768: 4 per head for 384 heads, 7-8 for 288).  With no more heads than
+// compute units the busiest unit decides: workgroups are dealt round-robin, so the cost is
+// the number of workgroups a unit gets times their length, and ties go to the fewer, longer
+// ones (measured at n = 32768, scoring and normalisation: 32 heads 8 per head, 64 heads 4,
+// 128 heads 2, 192 heads 4; 2 to 5 % faster than filling two workgroups per unit).
 static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
     const bool wide = ctx->cfg.dtype == CURDKV_DTYPE_BF16 && ctx->col_blocks > 2 && !ctx->cfg.no_projection;
     const int64_t stage = wide ? Stage<8>::kTiles : Stage<4>::kTiles;
-    const int64_t slots = (int64_t)ctx->num_cu * (wide ? 1 : 2);      // workgroups resident at a time
+    const int64_t slots = (int64_t)ctx->num_cu * ((wide || ctx->heads <= ctx->num_cu) ? 1 : 2);
     int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
     if (cap > kMaxBlocksPerHead) cap = kMaxBlocksPerHead;
     int64_t lo = (tiles + 4 * stage - 1) / (4 * stage);

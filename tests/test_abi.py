@@ -116,3 +116,93 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         B.Context(1, 1, 1, 128, 32, "bf16", 16, 1)
     with pytest.raises(RuntimeError):
         B.strerror(0)
+
+
+_SAN_HARNESS = r"""
+#include <cstdio>
+#include <cstring>
+#include <vector>
+#include "curdkv_internal.h"
+using namespace curdkv;
+int main() {
+    // for every (dtype, r): G of a few groups, packed into a buffer of exactly the packed size
+    // (the sanitizer puts red zones around it); prints a checksum of the values and of the packing
+    const int rs[] = {1, 20, 32, 33, 64, 100, 128};
+    for (int dtype = 0; dtype < 2; ++dtype)
+        for (int r : rs) {
+            curdkv_config cfg{};
+            cfg.layers = 3; cfg.kv_heads = 8; cfg.group_size = 4; cfg.head_dim = 128; cfg.sketch_dim = r;
+            cfg.dtype = dtype; cfg.max_tokens = 64; cfg.seed = 0xC0DE0003ull;
+            const int cbs = r <= 32 ? 1 : (r <= 64 ? 2 : 4);
+            std::vector<float> G((size_t)128 * r);
+            std::vector<unsigned char> packed(packed_elems(cbs) * (dtype == CURDKV_DTYPE_BF16 ? 2 : 4));
+            for (int l : {0, 2}) for (int h : {0, 7}) {
+                sketch_values(cfg, l, h, G.data());
+                pack_sketch(cfg, cbs, G.data(), packed.data());
+                unsigned long long a = 1469598103934665603ull, b = a;
+                for (float g : G) { unsigned u; std::memcpy(&u, &g, 4); a = (a ^ u) * 1099511628211ull; }
+                for (unsigned char c : packed) b = (b ^ c) * 1099511628211ull;
+                std::printf("%d %d %d %d %016llx %016llx\n", dtype, r, l, h, a, b);
+            }
+        }
+    return 0;
+}
+"""
+
+
+def _fnv(words, width):
+    a = 1469598103934665603
+    for w in words:
+        a = ((a ^ int(w)) * 1099511628211) & 0xFFFFFFFFFFFFFFFF
+    return a
+
+
+def test_sketch_host_code_under_address_and_ub_sanitizers(tmp_path):
+    # the host code that generates and packs the sketches, built for the CPU alone with
+    # AddressSanitizer and UBSan: no out-of-bounds access, no undefined arithmetic, and the
+    # values (against the oracle) and the operand packing (against the layout the kernels'
+    # comments state, written out here independently) are what they should be
+    import shutil
+    import subprocess
+    gxx = shutil.which("g++")
+    if gxx is None or not os.path.isdir("/opt/rocm/include"):
+        pytest.skip("needs g++ and the HIP headers")
+    src = tmp_path / "harness.cpp"
+    src.write_text(_SAN_HARNESS)
+    exe = tmp_path / "harness"
+    csrc = os.path.join(ROOT, "paper_2509_15038_amd", "csrc")
+    subprocess.run([gxx, "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                    "-static-libasan", "-static-libubsan",
+                    "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"), "-I", csrc, "-I", "/opt/rocm/include",
+                    os.path.join(csrc, "sketch_host.cpp"), str(src), "-o", str(exe)], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    p = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert p.returncode == 0, p.stderr[-3000:]
+    assert "runtime error" not in p.stderr and "AddressSanitizer" not in p.stderr, p.stderr[-3000:]
+    lines = [ln.split() for ln in p.stdout.strip().split("\n")]
+    assert len(lines) == 2 * 7 * 4
+    for dt, r, l, h, ha, hb in lines:
+        dt, r, l, h = int(dt), int(r), int(l), int(h)
+        dtype = "bf16" if dt == 1 else "fp32"
+        G = orc.sketch(0xC0DE0003, l, h, 8, 128, r, dtype).astype(np.float32)
+        assert int(ha, 16) == _fnv(G.reshape(-1).view(np.uint32), 4), (dtype, r, l, h)
+        cbs = 1 if r <= 32 else (2 if r <= 64 else 4)
+        Gp = np.zeros((128, 32 * cbs), dtype=np.float32)
+        Gp[:, :r] = G
+        if dtype == "bf16":
+            # [16-column block][step 0..3][lane][8 values]: rows s*32 + (lane//16)*8 + e, column cb*16 + lane%16
+            bits = orc.f32_to_bf16_bits(Gp)
+            out = np.empty((2 * cbs, 4, 64, 8), dtype=np.uint16)
+            for cb in range(2 * cbs):
+                for st in range(4):
+                    for lane in range(64):
+                        rows = st * 32 + (lane // 16) * 8 + np.arange(8)
+                        out[cb, st, lane] = bits[rows, cb * 16 + lane % 16]
+        else:
+            # [32-column block][step 0..63][lane]: row (lane//32)*64 + s, column cb*32 + lane%32
+            out = np.empty((cbs, 64, 64), dtype=np.float32)
+            for cb in range(cbs):
+                for st in range(64):
+                    lane = np.arange(64)
+                    out[cb, st] = Gp[(lane // 32) * 64 + st, cb * 32 + lane % 32]
+        assert int(hb, 16) == _fnv(out.reshape(-1).view(np.uint8), 1), ("packing", dtype, r, l, h)
