@@ -142,10 +142,11 @@ class Timer:
 
     def run(self, step, marks=2):
         import torch
+        # (the events are made before the warm-up so that the GPU does not sit idle, and clock
+        # down, between the warm-up and the timed steps)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(marks)] for _ in range(self.steps)]
         for _ in range(self.warmup):
             step(None)
-        torch.cuda.synchronize()
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(marks)] for _ in range(self.steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(self.steps):
@@ -239,9 +240,7 @@ def stream_rates(timer, cfg, Kd, Vd):
         _, seg = timer.run(step)
     ms = float(np.median(seg))
     out["copy_identity_gather"] = {"ms": ms, "GBps": heads * n * (4 + 4 * d * 2) / (ms * 1e-3) / 1e9}
-    del Ko, Vo, ident, scores
-    torch.cuda.empty_cache()
-    return out
+    return out, (Ko, Vo, ident, scores)           # kept alive by the caller: see the note on freeing in main()
 
 
 def summary(one, ab):
@@ -370,14 +369,6 @@ def main():
             o, c3, a = time_compress(ctx, timer, Kd, Vd, cfg, b, bufs)
             more[f"c3 keep={kp:g}"] = dict(summary(o, a), three_calls_ms=c3["ms_per_step"],
                                            traffic=measured_traffic("c3", kp, ctx.uses_fused_kernel(n) and int(b.sum()) * 4 <= heads * n, heads)[0])
-        rates = stream_rates(timer, cfg, Kd, Vd)
-        out["stream_rates_measured_in_this_run"] = rates
-        read = max(rates["read_keys_no_projection"]["GBps"], rates["read_keys_values_no_projection"]["GBps"])
-        copy = rates["copy_identity_gather"]["GBps"]
-        # time the same bytes would take as plain streams: the scan bytes at the better read rate,
-        # everything else (scores, indices, gathered rows) at the copy rate
-        out["roofline"]["frac_of_stream_rates"] = ((ab["scan"] / read + (ab["total"] - ab["scan"]) / copy) / 1e9
-                                                    / (kern_ms * 1e-3))
         c4 = wl.CONFIGS["c4"]
         K4, V4 = wl.device_cache(c4)
         b4 = wl.budgets_for(c4)
@@ -385,9 +376,18 @@ def main():
             o, c3, a = time_compress(ctx4, timer, K4, V4, c4, b4, bufs)
             more[f"c4 keep={c4.keep[0]:g}"] = dict(summary(o, a), three_calls_ms=c3["ms_per_step"],
                                                    traffic=measured_traffic("c4", c4.keep[0], True, heads)[0])
+        # (nothing is freed between the timed sections: the driver wipes freed device memory in
+        # the background, and for some hundred milliseconds after a free of several GiB every
+        # kernel here runs 3 to 4 % slower)
+        rates, keep_alive = stream_rates(timer, cfg, Kd, Vd)
+        out["stream_rates_measured_in_this_run"] = rates
+        read = max(rates["read_keys_no_projection"]["GBps"], rates["read_keys_values_no_projection"]["GBps"])
+        copy = rates["copy_identity_gather"]["GBps"]
+        # time the same bytes would take as plain streams: the scan bytes at the better read rate,
+        # everything else (scores, indices, gathered rows) at the copy rate
+        out["roofline"]["frac_of_stream_rates"] = ((ab["scan"] / read + (ab["total"] - ab["scan"]) / copy) / 1e9
+                                                    / (kern_ms * 1e-3))
         out["other_workloads"] = more
-        del K4, V4
-        torch.cuda.empty_cache()
 
     if args.adaptive is not None:
         kbase = int(np.sum(budgets) // heads)                   # the per-head budget the layers share out
@@ -418,21 +418,23 @@ def main():
         pm = np.array(parts).mean(0)
         # the same in one call, budgets and offsets staying on the device
         od = torch.empty((heads + 1,), dtype=torch.int64, device="cuda")
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        one_ms = []
-        for it in range(args.warmup + args.steps):
-            e0.record()
+        # (timed like the headline: the steps queued back to back, an event pair around each, so
+        # that the host's launch latency hides behind the previous step)
+        def step_ada(ev):
+            if ev:
+                ev[0].record()
             ctx.compress_adaptive(Kd, Vd, n, kbase, s, args.adaptive, scores, bd, od, ia, Ka, Va)
-            e1.record()
-            torch.cuda.synchronize()
-            if it >= args.warmup:
-                one_ms.append(e0.elapsed_time(e1))
+            if ev:
+                ev[1].record()
+        wall_ada, seg = timer.run(step_ada)
+        one_ms = seg[:, 0]
         assert bd.cpu().numpy().tolist() == ab_.tolist()
         out["adaptive"] = {"alpha": args.adaptive, "base_budget": kbase,
                            "ms": {"scores": float(pm[0]), "budgets_incl_copy": float(pm[1]),
                                   "select_incl_host_gap": float(pm[2]), "compact": float(pm[3]),
                                   "total": float(pm.sum())},
                            "one_call_ms": float(np.mean(one_ms)), "one_call_ms_median": float(np.median(one_ms)),
+                           "one_call_ms_per_step_wall": wall_ada,
                            "one_call_frac_of_hbm_peak": ab["total"] / (float(np.mean(one_ms)) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                            "budget_min_max": [int(ab_.min()), int(ab_.max())]}
     if args.append:
@@ -443,14 +445,14 @@ def main():
         res = {}
         for m in args.append:
             Kc, Vc = K4[:, :, n - m:].contiguous(), V4[:, :, n - m:].contiguous()
-            ts = []
-            for it in range(args.warmup + args.steps):
-                e0.record()
+            def step_app(ev, Kc=Kc, Vc=Vc, m=m):
+                if ev:
+                    ev[0].record()
                 ctx.scores_append(Kc, Vc, m, n - m, n, raw, sums)
-                e1.record()
-                torch.cuda.synchronize()
-                if it >= args.warmup:
-                    ts.append(e0.elapsed_time(e1))
+                if ev:
+                    ev[1].record()
+            _, seg = timer.run(step_app)
+            ts = seg[:, 0]
             bytes_m = heads * m * ((2 if args.source == "kv" else 1) * d * 2 + 4)
             res[str(m)] = {"ms": float(np.mean(ts)), "GBps": bytes_m / (np.mean(ts) * 1e-3) / 1e9,
                            "frac_of_hbm_peak": bytes_m / (np.mean(ts) * 1e-3) / 1e9 / HBM_PEAK_GBS}
