@@ -195,10 +195,11 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
 
 /* curdkv_adaptive_budgets for callers that cannot allocate device memory: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
- * Same arguments, same results, same kernels; the histograms and per-layer state
- * that curdkv_adaptive_budgets keeps in a buffer it allocates on first use live
- * here in a static device array of the library (24 MiB + 32 KiB per GPU, resident
- * from the moment the library is loaded, its address looked up at curdkv_create).
+ * Same arguments, same results, same kernels; the histograms, key lists and
+ * per-layer state that curdkv_adaptive_budgets keeps in a buffer its context got
+ * from hipMalloc live here in a static device array of the library (24 MiB +
+ * 32 KiB per GPU, resident from the moment the library is loaded, its address
+ * looked up at curdkv_create).
  * The call makes no hipMalloc, hipFree or other allocating call.
  * Limit: layers*kv_heads <= 1024, else CURDKV_ERR_TOO_LARGE and nothing is launched.
  * All calls on one GPU, from every context, share the one array: two such calls

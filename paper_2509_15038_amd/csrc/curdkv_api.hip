@@ -186,6 +186,14 @@ int curdkv_create(curdkv_ctx** out, const curdkv_config* cfg) {
         release(ctx);
         return CURDKV_ERR_OOM;
     }
+    // the head-wise budget allocation's workspace and its device-built gather table (a few
+    // tens of KB per head): allocated here so that the adaptive calls are kernel launches only
+    if (hipMalloc(&ctx->d_adaptive_ws, adaptive_workspace_bytes(ctx)) != hipSuccess ||
+        hipMalloc((void**)&ctx->d_adaptive_blocks, ctx->plan.max_blocks * sizeof(BlockInfo)) != hipSuccess) {
+        (void)hipGetLastError();
+        release(ctx);
+        return CURDKV_ERR_OOM;
+    }
     if (hipMalloc((void**)&ctx->d_zero_offsets, off_bytes) != hipSuccess ||
         hipMemset(ctx->d_zero_offsets, 0, off_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -363,11 +371,6 @@ int curdkv_adaptive_budgets(curdkv_ctx* ctx, const float* scores, int64_t n, int
     if (g > n - sp) g = n - sp;
     const long long H = ctx->cfg.kv_heads;
     const long long R = budget > sp ? H * ((long long)budget - sp) - H * g : 0;
-    if (!ctx->d_adaptive_ws && hipMalloc(&ctx->d_adaptive_ws, adaptive_workspace_bytes(ctx)) != hipSuccess) {
-        (void)hipGetLastError();
-        ctx->d_adaptive_ws = nullptr;
-        return CURDKV_ERR_OOM;
-    }
     return launch_adaptive(ctx, ctx->d_adaptive_ws, scores, n, budget, (int32_t)sp, (int32_t)g, R, budgets_out,
                            (hipStream_t)stream) == hipSuccess ? CURDKV_OK : CURDKV_ERR_HIP;
 }
@@ -412,17 +415,6 @@ int curdkv_compress_adaptive(curdkv_ctx* ctx, const void* K, const void* V, int6
             return CURDKV_ERR_OOM;
         }
         scores = ctx->d_scores_ws;
-    }
-    if (!ctx->d_adaptive_ws && hipMalloc(&ctx->d_adaptive_ws, adaptive_workspace_bytes(ctx)) != hipSuccess) {
-        (void)hipGetLastError();
-        ctx->d_adaptive_ws = nullptr;
-        return CURDKV_ERR_OOM;
-    }
-    if (!ctx->d_adaptive_blocks &&
-        hipMalloc((void**)&ctx->d_adaptive_blocks, ctx->plan.max_blocks * sizeof(BlockInfo)) != hipSuccess) {
-        (void)hipGetLastError();
-        ctx->d_adaptive_blocks = nullptr;
-        return CURDKV_ERR_OOM;
     }
     // normalised scores first: the allocation compares them across the heads of a layer.  The
     // fused kernel, where it applies, also leaves every head's key histogram in the workspace.

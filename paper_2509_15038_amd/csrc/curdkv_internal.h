@@ -56,8 +56,8 @@ struct curdkv_ctx {
     void* d_G = nullptr;               // packed sketches, storage type
     float* d_partial = nullptr;        // [heads, kMaxBlocksPerHead]
     int64_t* d_zero_offsets = nullptr; // [heads + 1] zeros: "keep nothing", for the scores-only use of the fused kernel
-    void* d_adaptive_ws = nullptr;     // histograms and per-layer state of curdkv_adaptive_budgets, on first use
-    curdkv::BlockInfo* d_adaptive_blocks = nullptr;  // gather block table built on the device (curdkv_compress_adaptive), on first use
+    void* d_adaptive_ws = nullptr;     // histograms, key segments and per-layer state of the head-wise budget allocation
+    curdkv::BlockInfo* d_adaptive_blocks = nullptr;  // gather block table built on the device (curdkv_compress_adaptive)
     float* d_scores_ws = nullptr;      // [heads, max_tokens], allocated when curdkv_compress needs it
     int lds_limit = 0;                 // max dynamic LDS per workgroup, bytes
     int num_cu = 0;
