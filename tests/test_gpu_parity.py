@@ -414,6 +414,47 @@ def test_adaptive_one_call_on_device(gu, layers, kv_heads, n, r, dtype):
             assert e.value.code == B.ERR_INVALID_ARG
 
 
+def test_adaptive_one_call_with_a_safeguarded_head(gu):
+    # one head of every layer has identical rows, hence equal scores 1/n: next to the peaked
+    # heads of its layer it stays below the layer's threshold and is kept alive by the safeguard
+    # alone.  Its selection cannot take the layer's threshold over and searches its own (among
+    # equal keys: the lowest token numbers), while the other heads of the layer do take it over.
+    import torch
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=32, n=3000 + 7)          # 256 heads: fused scoring phases
+    K, V = wl.host_cache(cfg)
+    L, H, n = cfg.layers, cfg.kv_heads, cfg.n
+    for l in range(L):
+        K[l, l % H] = K[l, l % H, 0]
+        V[l, l % H] = V[l, l % H, 0]
+    heads = L * H
+    k, s, alpha = n // 8, 4, 0.2
+    Kd, Vd = gu.to_device(K, "bf16"), gu.to_device(V, "bf16")
+    with B.Context(L, H, 4, 128, cfg.r, "bf16", n, cfg.sketch_seed) as ctx:
+        assert ctx.uses_fused_kernel(n)
+        sc = torch.empty((heads, n), dtype=torch.float32, device="cuda")
+        bd = torch.empty((heads,), dtype=torch.int32, device="cuda")
+        od = torch.empty((heads + 1,), dtype=torch.int64, device="cuda")
+        idx = torch.full((heads * k,), -1, dtype=torch.int32, device="cuda")
+        Ko = torch.zeros((heads * k, 128), dtype=torch.bfloat16, device="cuda"); Vo = torch.zeros_like(Ko)
+        ctx.compress_adaptive(Kd, Vd, n, k, s, alpha, sc, bd, od, idx, Ko, Vo)
+        torch.cuda.synchronize()
+        budgets, off, sc_h, idx_h = bd.cpu().numpy(), od.cpu().numpy(), sc.cpu().numpy(), idx.cpu().numpy()
+        Ko_h, Vo_h = gu.to_host(Ko, "bf16"), gu.to_host(Vo, "bf16")
+    g = int(np.floor(alpha * k))
+    for l in range(L):
+        lt = np.stack([orc.scores(orc.to_f64(K[l, h], "bf16"), orc.to_f64(V[l, h], "bf16"),
+                                  orc.sketch(cfg.sketch_seed, l, h, H, 128, cfg.r, "bf16")) for h in range(H)])
+        gu.check_adaptive_budgets(budgets[l * H:(l + 1) * H], lt, k, s, alpha, where=f"layer {l}")
+        flat = l * H + l % H
+        assert budgets[flat] == g, (l, budgets[l * H:(l + 1) * H])        # the safeguard, sinks included
+        assert idx_h[off[flat]:off[flat + 1]].tolist() == list(range(g))  # equal scores: lowest tokens
+        for h in range(H):
+            i = l * H + h
+            a, b = int(off[i]), int(off[i + 1])
+            gu.check_head(cfg, None, K[l, h], V[l, h], None, sc_h[i], idx_h[a:b], Ko_h[a:b], Vo_h[a:b],
+                          int(budgets[i]), s, where=f"l{l} h{h}", lt=lt[h])
+
+
 def test_adaptive_budgets_errors(gu):
     import torch
     with B.Context(1, 2, 4, 128, 64, "bf16", 64, 1) as ctx:
@@ -522,6 +563,58 @@ def test_select_adversarial_scores(gu, n):
         for h in range(H):
             want = orc.select(sc[h].astype(np.float64), int(b[h]), s)
             assert np.array_equal(idx[off[h]:off[h + 1]], want), (n, h, budgets)
+
+
+def _one_full_bin(rng, n, in_bin):
+    """Scores whose cut falls into a bin of the selection's 4096-bin histogram that holds exactly
+    `in_bin` keys: that many values 1 + i*2^-23 (one bin: 32 bins per binade), some of them equal,
+    a few thousand larger values, the rest spread far below."""
+    sc = (rng.random(n).astype(np.float32) * np.float32(0.4) + np.float32(1e-3))
+    where = rng.permutation(n)
+    sc[where[:in_bin]] = np.float32(1.0) + (rng.integers(0, max(in_bin // 3, 2), size=in_bin)).astype(np.float32) * np.float32(2.0 ** -23)
+    big = where[in_bin:in_bin + n // 50]
+    sc[big] = np.float32(1.5) + rng.random(big.size).astype(np.float32) * np.float32(0.4)
+    return sc, n // 50
+
+
+@pytest.mark.parametrize("n,in_bin", [(20000, 9999), (20000, 10000), (20000, 10001),      # registers: list of cap/2 = n/2 pairs
+                                      (36864, 16384), (36864, 16385),                     # cap bounded by LDS: 32768 words
+                                      (100000, 8192), (100000, 8193), (131072, 8000)])    # streaming: 8192 pairs
+def test_select_bin_capacity_boundaries(gu, n, in_bin):
+    # the usual route of the selection lists the keys inside the cut bin; a bin that holds one
+    # key more than the list takes goes the general route: both sides of every capacity, exact
+    import torch
+    rng = np.random.default_rng([n, in_bin])
+    H, s = 3, 4
+    sc = np.empty((H, n), dtype=np.float32)
+    budgets = []
+    for h in range(H):
+        sc[h], above = _one_full_bin(rng, n, in_bin)
+        budgets.append(s + above + [1, in_bin // 2, in_bin][h])       # cut at the top, middle and bottom of the bin
+    b = np.array(budgets, dtype=np.int32); off = wl.offsets_for(b)
+    with B.Context(1, H, 4, 128, 64, "bf16", n, 1) as ctx:
+        idx = torch.full((int(off[-1]),), -1, dtype=torch.int32, device="cuda")
+        ctx.select(torch.from_numpy(sc).cuda(), n, b, s, off, idx)
+        torch.cuda.synchronize()
+        idx = idx.cpu().numpy()
+    for h in range(H):
+        want = orc.select(sc[h].astype(np.float64), int(b[h]), s)
+        assert np.array_equal(idx[off[h]:off[h + 1]], want), (n, in_bin, h)
+
+
+@pytest.mark.parametrize("per_head", [511, 512, 513, 2048, 2049])
+def test_adaptive_list_capacity_boundaries(gu, per_head):
+    # the allocation's last workgroup resolves up to 4096 keys of the layer's cut bin in LDS
+    # (8 heads x 512) and each head hands in up to 2048: one key beyond either takes the general route
+    rng = np.random.default_rng(per_head)
+    H, n, s = 8, 12000, 4
+    sc = np.empty((2, H, n), dtype=np.float32)
+    for l in range(2):
+        for h in range(H):
+            sc[l, h], above = _one_full_bin(rng, n, per_head)
+    k = s + n // 50 + per_head // 2                      # the layer's cut lands inside the full bins
+    for alpha in (0.0, 0.2):
+        _ada_case(gu, sc, k, s, alpha)
 
 
 def test_eviction_loss_of_the_gpu_selection(gu):
