@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
         per_wave += per_wave & 1;                  // whole pairs
         const int32_t t_begin = wave * per_wave;
         const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
-        acc = scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane);
+        acc = scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n, t_begin, t_end, sc, 0, lane, scan_phase(head, wave));
     }
     // ---- 2. sum over the head ----------------------------------------------------------
     acc = wave_sum(acc);

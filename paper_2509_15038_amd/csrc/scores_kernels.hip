@@ -81,7 +81,8 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
     for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
         const int32_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
         const int32_t r0 = seg * kTileTokens;
-        acc_sum += scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane);
+        acc_sum += scan_tiles<CB, SRC, PROJ>(G, Kh, Vh, n32, seg, seg_end, mine, r0, lane,
+                                             scan_phase(head, blk * 4 + wave));
         const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
         for (int32_t r = r0 + lane; r < r1; r += 64) __builtin_nontemporal_store(mine[r - r0], &sh[r]);
     }
