@@ -160,6 +160,23 @@ def test_one_call_fused_long_heads(gu):
     gu.run_and_check(cfg, wl.budgets_for(cfg), one_call=True, fused=True)
 
 
+@pytest.mark.parametrize("n", [2048, 2040, 2560, 2464, 5120 + 31, 9 * 1024])
+def test_walk_start_rotation_range_lengths(gu, n):
+    # A wave walks its tile range from a start that depends on head and wave, when the range is
+    # whole pairs of whole tiles and at least 8 tiles long.  The sizes give the fused kernel's
+    # eight waves ranges of exactly 8 tiles (2048), 8 with a ragged last tile (2040: the last
+    # wave must not rotate), 10 (2560), 10 with an odd-length last range (2464 = 77 tiles), 22
+    # with a ragged end, and 36; the general kernel's 4 to 32 waves per head get other lengths
+    # from the same sizes.  Every score of every head is compared with the oracle, so a tile
+    # walked twice or left out shows.
+    cfg = wl.scaled(wl.CONFIGS["c3"], n=n)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.1), one_call=True, fused=True)
+    cfg = wl.scaled(wl.CONFIGS["c3"], layers=2, n=n)
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.1), one_call=False)
+    cfg = wl.scaled(wl.CONFIGS["c5"], layers=1, kv_heads=3, n=n)            # 128-column sketch
+    gu.run_and_check(cfg, wl.budgets_for(cfg, 0.1), one_call=False)
+
+
 @pytest.mark.parametrize("r", [20, 32, 64])
 def test_one_call_fused_sketch_dims(gu, r):
     cfg = wl.scaled(wl.CONFIGS["c3"], n=700, r=r)
