@@ -310,10 +310,14 @@ __global__ __launch_bounds__(kAdaThreads) void ada_resolve_kernel(
     // ---- the last workgroup of the layer to get here goes on; the others are done ---------------
     // One thread fences for the workgroup (the barrier orders the others' writes before its
     // fence, and after the count, its second fence before their reads): a fence at device scope
-    // is a cache-wide operation on this chip, far too dear to issue from every wave.
+    // is a cache-wide operation on this chip, far too dear to issue from every wave.  What every
+    // wave does do is wait until its own stores have been taken by the L2: the barrier by itself
+    // does not wait for stores in flight, and the one write-back must cover them all.
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (tid == 0) {
         __threadfence();                                        // the workgroup's writes, before the count
+        __builtin_amdgcn_s_waitcnt(0);                          // (the write-back itself included)
         const uint32_t old = atomicAdd(&ws.layer[layer].done, 1u);
         sm.last = old == (uint32_t)(H - 1) ? 1u : 0u;
         if (sm.last) __threadfence();                           // the other workgroups' writes, after the count
@@ -660,6 +664,9 @@ hipError_t launch_adaptive(const curdkv_ctx* ctx, void* workspace, const float* 
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    // the kernel keeps a head's first row inside its layer in 32 bits: a layer of 2^32 rows or
+    // more gets its offsets and block table from the general kernels instead
+    if ((long long)H * k > 0xFFFFFFFFll) offsets = nullptr;
     ada_resolve_kernel<<<dim3((unsigned)ctx->heads), kAdaThreads, kAdaResolveLds, stream>>>(
         ws, scores, n, H, sp, g, R, k, budgets, offsets, offsets ? block_info : nullptr, L);
     if (planned) *planned = offsets != nullptr;
