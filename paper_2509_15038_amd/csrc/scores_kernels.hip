@@ -211,7 +211,13 @@ __global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
 // compute units the busiest unit decides: workgroups are dealt round-robin, so the cost is
 // the number of workgroups a unit gets times their length, and ties go to the fewer, longer
 // ones (measured at n = 32768, scoring and normalisation: 32 heads 8 per head, 64 heads 4,
-// 128 heads 2, 192 heads 4; 2 to 5 % faster than filling two workgroups per unit).
+// 128 heads 2; 2 to 5 % faster than filling two workgroups per unit).
+// One exception, measured at n = 32768 with the two-per-unit kernel: where one workgroup per
+// head already puts four waves on three quarters of the compute units (192 or 224 heads of
+// 256, or 448 of 512 places), HBM is saturated by those alone, and one long-lived workgroup per
+// head, writing its scores in two bursts, beats any split by 2.5-3.5 % although units stay idle
+// (192 heads: 562 us against 576 for four per head; 224: 649 against 671; 448: 1305 against
+// 1338).
 static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
     const bool wide = ctx->cfg.dtype == CURDKV_DTYPE_BF16 && ctx->col_blocks > 2 && !ctx->cfg.no_projection;
@@ -222,6 +228,10 @@ static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     int64_t lo = (tiles + 4 * stage - 1) / (4 * stage);
     if (lo > cap) lo = cap;
     if (lo < 1) lo = 1;
+    if (!wide && lo <= 2 && ctx->heads <= 2 * (int64_t)ctx->num_cu) {
+        const int64_t in_last = ctx->heads - (ctx->heads > ctx->num_cu ? ctx->num_cu : 0);   // heads in the last round
+        if (in_last * 4 >= 3 * (int64_t)ctx->num_cu) return 1;
+    }
     const int64_t hi = lo + 15 < cap ? lo + 15 : cap;
     auto cost = [&](int64_t b) {                                       // rounds x tiles a wave works through
         const int64_t rounds = ((int64_t)ctx->heads * b + slots - 1) / slots;
