@@ -33,16 +33,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
+FP32_MFMA_PEAK_TFLOPS = 157.3     # MI355X, dense fp32 matrix rate
 
 
-def algorithmic_bytes(cfg, budgets, esize=2, source="kv"):
+def algorithmic_bytes(cfg, budgets, source="kv"):
     """Bytes the method has to move (per step and per part).  Per head: read K and
     V once (2*n*d*e; one of them only for the key-only / value-only ablation),
     write the scores (4n); select reads them (4n) and writes indices (4k); compact
     reads indices (4k), reads and writes k rows of K and V."""
     heads, n, d = cfg.layers * cfg.kv_heads, cfg.n, cfg.d
     ksum = int(np.sum(budgets.astype(np.int64)))
-    row = d * esize
+    row = d * (2 if cfg.dtype == "bf16" else 4)
     scan = heads * n * ((2 if source == "kv" else 1) * row)
     scores_call = scan + heads * n * 4
     select_call = heads * n * 4 + ksum * 4
@@ -262,6 +263,8 @@ def main():
                          "one GPU holds when the model's KV heads are spread over several")
     ap.add_argument("--tokens", type=int, default=None, help="tokens per head (default: the config's)")
     ap.add_argument("--sketch-dim", type=int, default=None, help="sketch width r (default: the config's)")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "fp32"],
+                    help="storage type of the cache (default: the config's; fp32 doubles the cache's bytes)")
     ap.add_argument("--source", default="kv", choices=["kv", "k", "v"],
                     help="ablation: score from keys and values (the method), keys only, values only")
     ap.add_argument("--no-projection", action="store_true", help="ablation: no Gaussian projection")
@@ -295,6 +298,8 @@ def main():
         cfg = wl.scaled(cfg, n=args.tokens)
     if args.sketch_dim is not None:
         cfg = wl.scaled(cfg, r=args.sketch_dim)
+    if args.dtype is not None:
+        cfg = wl.scaled(cfg, dtype=args.dtype)
     keep = cfg.keep[0] if args.keep is None else args.keep
     budgets = wl.budgets_for(cfg, keep)
     total = int(budgets.astype(np.int64).sum())
@@ -302,14 +307,15 @@ def main():
     heads = L * H
     plain = args.source == "kv" and not args.no_projection
     extras = (plain and not args.headline_only and args.config == "c3" and args.keep is None
-              and args.layers is None and args.tokens is None and args.sketch_dim is None)
+              and args.layers is None and args.tokens is None and args.sketch_dim is None
+              and args.dtype is None)
 
     Kd, Vd = wl.device_cache(cfg)
     rows_max = max(total, int(heads * n * 0.5) if extras else 0, 1)
     scores = torch.empty((heads, n), dtype=torch.float32, device="cuda")
     indices = torch.empty((rows_max,), dtype=torch.int32, device="cuda")
-    Ko = torch.empty((rows_max, d), dtype=torch.bfloat16, device="cuda")
-    Vo = torch.empty((rows_max, d), dtype=torch.bfloat16, device="cuda")
+    Ko = torch.empty((rows_max, d), dtype=Kd.dtype, device="cuda")
+    Vo = torch.empty((rows_max, d), dtype=Kd.dtype, device="cuda")
     bufs = (scores, indices, Ko, Vo)
     ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed, args.source,
                     not args.no_projection)
@@ -331,7 +337,9 @@ def main():
     kv_tokens = heads * n
     value = kv_tokens / (ms_per_step * 1e-3)
     kern_gbs = ab["total"] / (kern_ms * 1e-3) / 1e9
-    traffic, traffic_src = measured_traffic(cfg.name, keep, fused, heads) if plain else (None, None)
+    # (the profile summaries cover the configurations' own n, r and storage type, any head count)
+    as_profiled = plain and args.tokens is None and args.sketch_dim is None and args.dtype is None
+    traffic, traffic_src = measured_traffic(cfg.name, keep, fused, heads) if as_profiled else (None, None)
     out = {
         "metric": "KV tokens scored+compacted/sec at 8B shape, 32k ctx; % of HBM peak",
         "value": value, "unit": "KV tokens/s (one token of one layer and KV head)",
@@ -359,6 +367,20 @@ def main():
                      "max_ms": one["ms_max_events"]},
         "three_calls": calls,
     }
+
+    # An fp32 cache with a wide sketch is bound by the fp32 matrix rate, not by HBM: 4*d*r flop per
+    # token (2*d*r for key-only / value-only) against 8*d bytes.  The scoring kernel is then the
+    # dominant one and is priced against the fp32 MFMA peak; the HBM view stays beside it.
+    if cfg.dtype == "fp32" and not args.no_projection:
+        flops = (4 if args.source == "kv" else 2) * d * cfg.r * heads * n
+        if flops / (FP32_MFMA_PEAK_TFLOPS * 1e12) > ab["total"] / (HBM_PEAK_GBS * 1e9):
+            sc_ms = calls["ms"]["scores"]
+            tf = flops / (sc_ms * 1e-3) / 1e12
+            out["roofline"] = {"bound": "mfma", "kernel": "scores_f32_kernel (curdkv_scores: scoring kernel + normalisation)",
+                               "achieved": tf, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                               "frac": tf / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                               "algorithmic_flops_per_launch": flops, "avg_ms": sc_ms,
+                               "whole_path_against_hbm": out["roofline"]}
 
     if extras:
         # the rest of the headline configuration, driver-visible: the other two budgets on the same

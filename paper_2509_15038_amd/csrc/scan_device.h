@@ -114,6 +114,63 @@ __device__ __forceinline__ uint32_t scan_phase(int head, int wave_of_head) {
     return (uint32_t)head * 5u + (uint32_t)wave_of_head * 3u;
 }
 
+// The walk over tiles [t_begin, t_end) of one wave, shared by the storage types: two tile
+// buffers, tiles taken in pairs.
+//   load_tile(Tile&, tile, check)   issues the loads of one tile; check = std::true_type clamps
+//                                   rows to n - 1 (a ragged last tile), std::false_type is for
+//                                   tiles known to lie entirely below n: no clamping, no
+//                                   predicate, hence no branch, which keeps the steady-state
+//                                   loop one basic block so that the compiler's wait counts let
+//                                   loads stay in flight;
+//   compute_tile(const Tile&, slot) scores the tile as first (0) or second (1) of its pair;
+//   store_pair(tile, check)         puts the pair's 64 scores away (tile = its first tile).
+// t_begin must be even, and t_end even or equal to ceil(n/32): a missing second tile is taken
+// to lie beyond n.
+template <class Tile, class Load, class Compute, class Store>
+__device__ __forceinline__ void walk_tiles(int32_t n, int32_t t_begin, int32_t t_end, uint32_t phase,
+                                           Load load_tile, Compute compute_tile, Store store_pair) {
+    const std::true_type checked;
+    const std::false_type unchecked;
+    if (t_begin < t_end) {
+        Tile ra, rb;
+        const int32_t full = n / kTileTokens;                   // tiles with all 32 rows below n
+        // The walk starts at tile t_begin + rot and wraps at t_end; rot follows from the caller's
+        // phase.  Heads lie a power of two apart in memory, so waves of different heads that walk
+        // from the same offset of their ranges keep asking the same memory channels for different
+        // rows; started at different offsets they stream 2-3 % faster (measured, 256 heads of
+        // 32768 tokens).  Only ranges of whole pairs of whole tiles are rotated, by whole pairs.
+        const int32_t len = t_end - t_begin;
+        const int32_t rot = (t_end <= full && !(len & 1) && len >= 8) ? (int32_t)(phase % (uint32_t)(len >> 1)) * 2 : 0;
+        auto at = [&](int32_t i) -> int32_t { const int32_t t = i + rot; return t >= t_end ? t - len : t; };
+        int32_t t = t_begin;
+        // both buffers are always filled (a lone tile is simply loaded twice): a
+        // conditional load here would make every wait in the loop below pessimistic
+        load_tile(ra, at(t), checked);
+        load_tile(rb, t + 1 < t_end ? at(t + 1) : at(t), checked);
+        const int32_t t_steady = t_end < full ? t_end : full;
+        for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 of the walk are whole
+            compute_tile(ra, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(ra, at(t + 2), unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_tile(rb, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_tile(rb, at(t + 3), unchecked);
+            store_pair(at(t), unchecked);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (; t < t_end; t += 2) {                             // last one or two pairs
+            compute_tile(ra, 0);
+            if (t + 2 < t_end) load_tile(ra, at(t + 2), checked);
+            if (t + 1 < t_end) {
+                compute_tile(rb, 1);
+                if (t + 3 < t_end) load_tile(rb, at(t + 3), checked);
+            }
+            store_pair(at(t), checked);                         // an absent second tile lies beyond n
+        }
+    }
+}
+
 template <int CB, int SRC = kSrcKV, bool PROJ = true>
 __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4* __restrict__ Kh,
                                             const uint4* __restrict__ Vh, int32_t n, int32_t t_begin,
@@ -123,9 +180,6 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
     float acc_sum = 0.f;
     float pend = 0.f;                                           // this lane's score of the current pair
 
-    // CHECK = false is for tiles known to lie entirely below n: no clamping, no
-    // predicate, hence no branch, which keeps the steady-state loop one basic
-    // block so that the compiler's wait counts let loads stay in flight.
     auto load_tile = [&](TileRegs& r, int32_t tile, auto check) {
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
@@ -187,47 +241,101 @@ __device__ __forceinline__ float scan_tiles(const SketchRegs<CB>& G, const uint4
             acc_sum += pend;
         }
     };
-    const std::true_type checked;
-    const std::false_type unchecked;
+    walk_tiles<TileRegs>(n, t_begin, t_end, phase, load_tile, compute_tile, store_pair);
+    return acc_sum;
+}
 
-    if (t_begin < t_end) {
-        TileRegs ra, rb;
-        const int32_t full = n / kTileTokens;                   // tiles with all 32 rows below n
-        // The walk starts at tile t_begin + rot and wraps at t_end; rot follows from the caller's
-        // phase.  Heads lie a power of two apart in memory, so waves of different heads that walk
-        // from the same offset of their ranges keep asking the same memory channels for different
-        // rows; started at different offsets they stream 2-3 % faster (measured, 256 heads of
-        // 32768 tokens).  Only ranges of whole pairs of whole tiles are rotated, by whole pairs.
-        const int32_t len = t_end - t_begin;
-        const int32_t rot = (t_end <= full && !(len & 1) && len >= 8) ? (int32_t)(phase % (uint32_t)(len >> 1)) * 2 : 0;
-        auto at = [&](int32_t i) -> int32_t { const int32_t t = i + rot; return t >= t_end ? t - len : t; };
-        int32_t t = t_begin;
-        // both buffers are always filled (a lone tile is simply loaded twice): a
-        // conditional load here would make every wait in the loop below pessimistic
-        load_tile(ra, at(t), checked);
-        load_tile(rb, t + 1 < t_end ? at(t + 1) : at(t), checked);
-        const int32_t t_steady = t_end < full ? t_end : full;
-        for (; t + 4 <= t_steady; t += 2) {                     // tiles t .. t+3 of the walk are whole
-            compute_tile(ra, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(ra, at(t + 2), unchecked);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_tile(rb, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_tile(rb, at(t + 3), unchecked);
-            store_pair(at(t), unchecked);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        for (; t < t_end; t += 2) {                             // last one or two pairs
-            compute_tile(ra, 0);
-            if (t + 2 < t_end) load_tile(ra, at(t + 2), checked);
-            if (t + 1 < t_end) {
-                compute_tile(rb, 1);
-                if (t + 3 < t_end) load_tile(rb, at(t + 3), checked);
+// ---- fp32 storage -----------------------------------------------------------------------
+// The same walk and the same lane roles as above with mfma_f32_16x16x4f32: lane L holds token
+// L%16 and, of every 64-byte stretch of its row, the 16 bytes (four floats) number L/16, so a
+// load instruction again asks for 64 contiguous bytes per row.  One MFMA takes one of the four
+// floats as the token operand; its sketch operand in lane L is
+// G[(4*s + L/16)*4 + e][16*cb + L%16] for step s = 0..7 and float e = 0..3.  The sketch lives
+// in registers up to 64 columns (32*CB floats per lane) and in LDS beyond (gs: the packed
+// sketch as it lies in memory, [cb][s][lane] float4).
+struct TileRegsF32 {    // one 32-token tile of K and of V as seen by a lane
+    float4 k[2][8];
+    float4 v[2][8];
+};
+
+template <int CB, bool IN_REGS>
+struct SketchF32 {
+    float4 g[IN_REGS ? CB : 1][8];
+};
+
+template <int CB, bool IN_REGS, int SRC = kSrcKV>
+__device__ __forceinline__ float scan_tiles_f32(const SketchF32<CB, IN_REGS>& G, const float4* __restrict__ gs,
+                                                const float4* __restrict__ Kh, const float4* __restrict__ Vh,
+                                                int32_t n, int32_t t_begin, int32_t t_end, float* lds_rows,
+                                                int32_t row0, int lane, uint32_t phase = 0) {
+    const int tok = lane & 15, q = lane >> 4;
+    float acc_sum = 0.f;
+    float pend = 0.f;
+    auto load_tile = [&](TileRegsF32& r, int32_t tile, auto check) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            int32_t row = tile * kTileTokens + t2 * 16 + tok;
+            if (decltype(check)::value) row = row < n ? row : n - 1;
+            const size_t off = (size_t)(uint32_t)row * 32 + q;          // 32 float4 per row
+            const float4* kp = Kh + off;
+            const float4* vp = Vh + off;
+            if (SRC != kSrcV) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) r.k[t2][s] = kp[s * 4];
             }
-            store_pair(at(t), checked);                         // an absent second tile lies beyond n
+            if (SRC != kSrcK) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s) r.v[t2][s] = vp[s * 4];
+            }
         }
-    }
+    };
+    auto compute_tile = [&](const TileRegsF32& r, int slot) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            float lk = SRC == kSrcV ? 0.25f : 0.f, lv = SRC == kSrcK ? 0.25f : 0.f;
+            // a sketch in LDS is read again for every sub-tile: the lane's offset is made opaque
+            // here, or the compiler lifts all of the loads out of the walk and runs out of registers
+            int gl = lane;
+            if (!IN_REGS) asm volatile("" : "+v"(gl));
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    const float4 g = IN_REGS ? G.g[IN_REGS ? cb : 0][s] : gs[(cb * 8 + s) * 64 + gl];
+                    if (SRC != kSrcV) {
+                        const float4 x = r.k[t2][s];
+                        ak = __builtin_amdgcn_mfma_f32_16x16x4f32(g.x, x.x, ak, 0, 0, 0);
+                        ak = __builtin_amdgcn_mfma_f32_16x16x4f32(g.y, x.y, ak, 0, 0, 0);
+                        ak = __builtin_amdgcn_mfma_f32_16x16x4f32(g.z, x.z, ak, 0, 0, 0);
+                        ak = __builtin_amdgcn_mfma_f32_16x16x4f32(g.w, x.w, ak, 0, 0, 0);
+                    }
+                    if (SRC != kSrcK) {
+                        const float4 x = r.v[t2][s];
+                        av = __builtin_amdgcn_mfma_f32_16x16x4f32(g.x, x.x, av, 0, 0, 0);
+                        av = __builtin_amdgcn_mfma_f32_16x16x4f32(g.y, x.y, av, 0, 0, 0);
+                        av = __builtin_amdgcn_mfma_f32_16x16x4f32(g.z, x.z, av, 0, 0, 0);
+                        av = __builtin_amdgcn_mfma_f32_16x16x4f32(g.w, x.w, av, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (SRC != kSrcV) lk = fmaf(ak[e], ak[e], lk);
+                    if (SRC != kSrcK) lv = fmaf(av[e], av[e], lv);
+                }
+            }
+            const float lkv = combine_rows(lk, lv);
+            pend = (q == slot * 2 + t2) ? lkv : pend;
+        }
+    };
+    auto store_pair = [&](int32_t tile, auto check) {
+        const int32_t row = tile * kTileTokens + lane;
+        if (!decltype(check)::value || row < n) {
+            lds_rows[row - row0] = pend;
+            acc_sum += pend;
+        }
+    };
+    walk_tiles<TileRegsF32>(n, t_begin, t_end, phase, load_tile, compute_tile, store_pair);
     return acc_sum;
 }
 

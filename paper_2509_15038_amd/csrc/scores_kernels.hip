@@ -13,15 +13,6 @@
 
 namespace curdkv {
 
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-__device__ __forceinline__ float sum_sq(const f32x16& a) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s = fmaf(a[i], a[i], s);
-    return s;
-}
-
 // Sum the four wave totals of a 256-thread block in a fixed order and store it.  A head
 // scored by a single block (few new tokens during generation) can fold the total into the
 // head's running sum right here: sum = (restart ? 0 : sum) + total, in double, which is
@@ -91,62 +82,60 @@ __global__ __launch_bounds__(256, (CB <= 4 ? 2 : 1)) void scores_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// fp32 storage (small caches): mfma_f32_32x32x2f32, the sketch staged in LDS.
-// Lane L owns token L%32 and the 64 contiguous floats of half row L/32.
+// fp32 storage: the same structure with mfma_f32_16x16x4f32 (scan_device.h).  A lane's two
+// tile buffers take 256 registers, so a SIMD holds one wave and a compute unit one workgroup.
+// CB = 16-column blocks of the padded sketch: 2 and 4 keep the sketch in registers, 8 reads it
+// from LDS.  Up to 32 columns the kernel is bound by HBM, from 64 on by the fp32 matrix rate
+// (4*d*r flop per 1024 bytes of a token's K and V rows is 32 flop/B at r = 64).
 // ---------------------------------------------------------------------------
-template <int CB>
-__global__ __launch_bounds__(256) void scores_f32_kernel(
-    const float4* __restrict__ K, const float4* __restrict__ V, const float* __restrict__ Gp,
+template <int CB> struct StageF32 {
+    static constexpr int kTiles = CB > 4 ? 128 : 256;     // 64 KB beside a 64 KB sketch, else 128 KB
+};
+
+template <int CB, int SRC>
+__global__ __launch_bounds__(256, 1) void scores_f32_kernel(
+    const float4* __restrict__ K, const float4* __restrict__ V, const float4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
-    int source, int64_t out_stride, int64_t out_offset, double* __restrict__ sums, int restart) {
-    extern __shared__ float gs[];                      // [CB][64 steps][64 lanes]
+    int64_t out_stride, int64_t out_offset, double* __restrict__ sums, int restart) {
+    constexpr bool kInRegs = CB <= 4;
+    constexpr int kStageTiles = StageF32<CB>::kTiles;
+    __shared__ float stage[4][kStageTiles * kTileTokens];
+    __shared__ float4 gs[kInRegs ? 1 : CB * 8 * 64];
     const int head = blockIdx.x / blocks_per_head;
     const int blk = blockIdx.x - head * blocks_per_head;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tok = lane & 31, half = lane >> 5;
 
-    for (int i = threadIdx.x; i < CB * 4096; i += 256) gs[i] = Gp[(size_t)head * (CB * 4096) + i];
-    __syncthreads();
+    const float4* Gh = Gp + (size_t)head * (CB * 8 * 64);
+    SketchF32<CB, kInRegs> G;
+    if (kInRegs) {
+#pragma unroll
+        for (int cb = 0; cb < (kInRegs ? CB : 1); ++cb)
+#pragma unroll
+            for (int s = 0; s < 8; ++s) G.g[cb][s] = Gh[(cb * 8 + s) * 64 + lane];
+    } else {
+        for (int i = threadIdx.x; i < CB * 8 * 64; i += 256) gs[i] = Gh[i];
+        __syncthreads();
+    }
 
-    const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
-    const int64_t stride = (int64_t)blocks_per_head * 4;
-    const float4* Kh = K + (size_t)head * n * 32;      // 32 float4 per row
+    const int32_t n32 = (int32_t)n;
+    const int32_t tiles = (n32 + kTileTokens - 1) / kTileTokens;
+    const int32_t waves_per_head = blocks_per_head * 4;
+    int32_t per_wave = (tiles + waves_per_head - 1) / waves_per_head;
+    per_wave += per_wave & 1;                                   // whole pairs
+    const int32_t t_begin = (blk * 4 + wave) * per_wave;
+    const int32_t t_end = t_begin + per_wave < tiles ? t_begin + per_wave : tiles;
+    const float4* Kh = K + (size_t)head * n * 32;               // 32 chunks of 16 bytes per row
     const float4* Vh = V + (size_t)head * n * 32;
     float* sh = scores + (size_t)head * out_stride + out_offset;
-
+    float* mine = stage[wave];
     float acc_sum = 0.f;
-    for (int64_t tile = (int64_t)blk * 4 + wave; tile < tiles; tile += stride) {
-        const int64_t row = tile * kTileTokens + tok;
-        const int64_t rowc = row < n ? row : n - 1;
-        float l[2];
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
-            const float4* p = (which == 0 ? Kh : Vh) + rowc * 32 + half * 16;
-            float4 x[16];
-#pragma unroll
-            for (int q = 0; q < 16; ++q) x[q] = p[q];
-            float tot = 0.f;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                f32x16 a = {0};
-                const float* gq = gs + cb * 4096 + lane;
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 0) * 64], x[q].x, a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 1) * 64], x[q].y, a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 2) * 64], x[q].z, a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_32x32x2f32(gq[(4 * q + 3) * 64], x[q].w, a, 0, 0, 0);
-                }
-                tot += sum_sq(a);
-            }
-            tot += __shfl_xor(tot, 32, 64);
-            l[which] = tot;
-        }
-        const float lkv = source == CURDKV_SCORE_KV ? l[0] * l[1] : (source == CURDKV_SCORE_KEY ? l[0] : l[1]);
-        if (half == 0 && row < n) {
-            sh[row] = lkv;
-            acc_sum += lkv;
-        }
+    for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
+        const int32_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
+        const int32_t r0 = seg * kTileTokens;
+        acc_sum += scan_tiles_f32<CB, kInRegs, SRC>(G, gs, Kh, Vh, n32, seg, seg_end, mine, r0, lane,
+                                                    scan_phase(head, blk * 4 + wave));
+        const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
+        for (int32_t r = r0 + lane; r < r1; r += 64) __builtin_nontemporal_store(mine[r - r0], &sh[r]);
     }
     block_partial_store(wave_sum(acc_sum), partial + (size_t)head * kMaxBlocksPerHead + blk,
                         sums ? sums + head : nullptr, restart);
@@ -221,14 +210,16 @@ __global__ __launch_bounds__(256) void fold_kernel(const float* __restrict__ sq,
 static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
     const bool wide = ctx->cfg.dtype == CURDKV_DTYPE_BF16 && ctx->col_blocks > 2 && !ctx->cfg.no_projection;
-    const int64_t stage = wide ? Stage<8>::kTiles : Stage<4>::kTiles;
-    const int64_t slots = (int64_t)ctx->num_cu * ((wide || ctx->heads <= ctx->num_cu) ? 1 : 2);
+    const bool f32 = ctx->cfg.dtype == CURDKV_DTYPE_F32;         // one workgroup per compute unit, like the wide kernel
+    const int64_t stage = f32 ? (ctx->col_blocks > 2 ? StageF32<8>::kTiles : StageF32<4>::kTiles)
+                              : (wide ? Stage<8>::kTiles : Stage<4>::kTiles);
+    const int64_t slots = (int64_t)ctx->num_cu * ((wide || f32 || ctx->heads <= ctx->num_cu) ? 1 : 2);
     int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
     if (cap > kMaxBlocksPerHead) cap = kMaxBlocksPerHead;
     int64_t lo = (tiles + 4 * stage - 1) / (4 * stage);
     if (lo > cap) lo = cap;
     if (lo < 1) lo = 1;
-    if (!wide && lo <= 2 && ctx->heads <= 2 * (int64_t)ctx->num_cu) {
+    if (!wide && !f32 && lo <= 2 && ctx->heads <= 2 * (int64_t)ctx->num_cu) {
         const int64_t in_last = ctx->heads - (ctx->heads > ctx->num_cu ? ctx->num_cu : 0);   // heads in the last round
         if (in_last * 4 >= 3 * (int64_t)ctx->num_cu) return 1;
     }
@@ -247,16 +238,7 @@ static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
 }
 
 hipError_t configure_kernels(curdkv_ctx* ctx) {
-    if (ctx->cfg.dtype == CURDKV_DTYPE_F32) {
-        const int bytes = ctx->col_blocks * 4096 * 4;
-        hipError_t e = hipSuccess;
-        switch (ctx->col_blocks) {
-            case 1: e = hipFuncSetAttribute((const void*)scores_f32_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
-            case 2: e = hipFuncSetAttribute((const void*)scores_f32_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
-            default: e = hipFuncSetAttribute((const void*)scores_f32_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); break;
-        }
-        return e;
-    }
+    (void)ctx;                     // every scoring kernel uses static LDS only
     return hipSuccess;
 }
 
@@ -294,14 +276,23 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
 #undef CURDKV_BY_SRC
 #undef CURDKV_LAUNCH
     } else {
-        const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float* g = (const float*)ctx->d_G;
-        const size_t lds = (size_t)ctx->col_blocks * 4096 * 4;
-        const int src = ctx->cfg.score_source;
-        switch (ctx->col_blocks) {
-            case 1: scores_f32_kernel<1><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
-            case 2: scores_f32_kernel<2><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
-            default: scores_f32_kernel<4><<<grid, block, lds, stream>>>(k, v, g, scores, ctx->d_partial, n, bph, src, out_stride, out_offset, sums, rs); break;
+        const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float4* g = (const float4*)ctx->d_G;
+        float* part = ctx->d_partial;
+#define CURDKV_LAUNCH(CBV, SRCV) \
+    scores_f32_kernel<CBV, SRCV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset, sums, rs)
+#define CURDKV_BY_SRC(CBV)                                                          \
+    switch (ctx->cfg.score_source) {                                                \
+        case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK); break;                    \
+        case CURDKV_SCORE_VALUE: CURDKV_LAUNCH(CBV, kSrcV); break;                  \
+        default: CURDKV_LAUNCH(CBV, kSrcKV); break;                                 \
+    }
+        switch (ctx->col_blocks) {       // 16-column MFMA blocks = 2 per 32 padded columns
+            case 1: CURDKV_BY_SRC(2) break;
+            case 2: CURDKV_BY_SRC(4) break;
+            default: CURDKV_BY_SRC(8) break;
         }
+#undef CURDKV_BY_SRC
+#undef CURDKV_LAUNCH
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || !normalise) return e;

@@ -72,9 +72,11 @@ size_t packed_elems(int col_blocks) { return static_cast<size_t>(col_blocks) * 4
 //   mfma_f32_16x16x32_bf16 whose A operand in lane L is the 8 values
 //   G[s*32 + (L/16)*8 + e][cb*16 + L%16], e = 0..7  (the token operand of lane L
 //   is the 16-byte chunk s*4 + L/16 of token L%16).
-// fp32: per 32-column block cb and step s (0..63) one mfma_f32_32x32x2f32 whose
-//   A operand in lane L is G[(L/32)*64 + s][cb*32 + L%32]  (the token operand of
-//   lane L comes from the contiguous half row L/32 of token L%32).
+// fp32: per 16-column block cb, step s (0..7) and e (0..3) one mfma_f32_16x16x4f32
+//   whose A operand in lane L is G[(s*4 + L/16)*4 + e][cb*16 + L%16]  (the token
+//   operand of lane L is float e of the 16-byte chunk s*4 + L/16 of token L%16);
+//   the four values of a lane for one (cb, s) lie together, so a lane loads them
+//   as one 16-byte word.
 void pack_sketch(const curdkv_config& cfg, int col_blocks, const float* G, void* packed) {
     const int r = cfg.sketch_dim;
     auto at = [&](int row, int col) -> float { return col < r ? G[row * r + col] : 0.0f; };
@@ -88,10 +90,11 @@ void pack_sketch(const curdkv_config& cfg, int col_blocks, const float* G, void*
                             bf16_bits_rne(at(s * 32 + (lane / 16) * 8 + e, cb * 16 + lane % 16));
     } else {
         float* out = static_cast<float*>(packed);
-        for (int cb = 0; cb < col_blocks; ++cb)
-            for (int s = 0; s < 64; ++s)
+        for (int cb = 0; cb < 2 * col_blocks; ++cb)
+            for (int s = 0; s < 8; ++s)
                 for (int lane = 0; lane < 64; ++lane)
-                    out[(cb * 64 + s) * 64 + lane] = at((lane / 32) * 64 + s, cb * 32 + lane % 32);
+                    for (int e = 0; e < 4; ++e)
+                        out[((cb * 8 + s) * 64 + lane) * 4 + e] = at((s * 4 + lane / 16) * 4 + e, cb * 16 + lane % 16);
     }
 }
 

@@ -160,12 +160,13 @@ def host_cache(cfg: Config):
 def device_cache(cfg: Config, device="cuda:0"):
     """(K, V) torch tensors [layers, kv_heads, n, d] drawn on the GPU, layer by
     layer, from the same distributions as `host_head` (different bits: torch's
-    generator).  Only the "llm" recipe at bf16 is needed at these sizes."""
+    generator).  Only the "llm" recipe is needed at these sizes."""
     import torch
-    assert cfg.recipe == "llm" and cfg.dtype == "bf16"
+    assert cfg.recipe == "llm" and cfg.dtype in ("bf16", "fp32")
     L, H, n, d = cfg.layers, cfg.kv_heads, cfg.n, cfg.d
-    K = torch.empty((L, H, n, d), dtype=torch.bfloat16, device=device)
-    V = torch.empty((L, H, n, d), dtype=torch.bfloat16, device=device)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    K = torch.empty((L, H, n, d), dtype=tdt, device=device)
+    V = torch.empty((L, H, n, d), dtype=tdt, device=device)
     g = torch.Generator(device=device)
     g.manual_seed(0x5EED0000 + cfg.cfg_id)
     rows = 8192 if n > 8192 else n
@@ -183,6 +184,6 @@ def device_cache(cfg: Config, device="cuda:0"):
                 p = min(cfg.prefix_rows, r1) - r0
                 k[:, :p] *= cfg.prefix_scale
                 v[:, :p] *= cfg.prefix_scale
-            K[l, :, r0:r1] = k.to(torch.bfloat16)
-            V[l, :, r0:r1] = v.to(torch.bfloat16)
+            K[l, :, r0:r1] = k.to(tdt)
+            V[l, :, r0:r1] = v.to(tdt)
     return K, V

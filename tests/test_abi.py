@@ -199,10 +199,11 @@ def test_sketch_host_code_under_address_and_ub_sanitizers(tmp_path):
                         rows = st * 32 + (lane // 16) * 8 + np.arange(8)
                         out[cb, st, lane] = bits[rows, cb * 16 + lane % 16]
         else:
-            # [32-column block][step 0..63][lane]: row (lane//32)*64 + s, column cb*32 + lane%32
-            out = np.empty((cbs, 64, 64), dtype=np.float32)
-            for cb in range(cbs):
-                for st in range(64):
-                    lane = np.arange(64)
-                    out[cb, st] = Gp[(lane // 32) * 64 + st, cb * 32 + lane % 32]
+            # [16-column block][step 0..7][lane][4 values]: rows (s*4 + lane//16)*4 + e, column cb*16 + lane%16
+            out = np.empty((2 * cbs, 8, 64, 4), dtype=np.float32)
+            for cb in range(2 * cbs):
+                for st in range(8):
+                    for lane in range(64):
+                        rows = (st * 4 + lane // 16) * 4 + np.arange(4)
+                        out[cb, st, lane] = Gp[rows, cb * 16 + lane % 16]
         assert int(hb, 16) == _fnv(out.reshape(-1).view(np.uint8), 1), ("packing", dtype, r, l, h)
