@@ -79,7 +79,7 @@ typedef struct curdkv_config {
     int32_t  dtype;        /* CURDKV_DTYPE_* : storage type of K, V and of G */
     int32_t  score_source; /* CURDKV_SCORE_* ; 0 = the method's key-value product */
     int32_t  no_projection;/* 0 = sketch with G (the method); 1 = the ablation without the Gaussian
-                              projection: squared norms of the stored rows (bf16 only) */
+                              projection: squared norms of the stored rows */
     int64_t  max_tokens;   /* largest n any call will pass, >= 1 */
     uint64_t seed;         /* seed of the sketch generator */
 } curdkv_config;

@@ -589,6 +589,13 @@ constexpr size_t kAdaLastLds = ((size_t)kAdaDigWords + 3 * (size_t)kAdaMaxHeads 
 constexpr size_t kAdaOwnLds = (size_t)kAdaOwn * kAdaThreads * 4;
 constexpr size_t kAdaResolveLds = kAdaOwnLds > kAdaLastLds ? kAdaOwnLds : kAdaLastLds;
 
+// The layout above holds for every head count the kernel accepts: digit histograms of at least
+// one bit per level, and everything inside the 160 KB of a gfx950 workgroup beside the static
+// part (AdaShared and the compiler's own few words).
+static_assert((kAdaMaxHeads << 1) <= kAdaDigWords, "a level of one bit must fit the digit histograms");
+static_assert(kAdaResolveLds + sizeof(AdaShared) + 1024 <= 160 * 1024, "ada_resolve_kernel's LDS");
+static_assert(kAdaSeg <= kAdaList, "one head's segment must fit the list");
+
 hipError_t configure_adaptive(curdkv_ctx* ctx) {
     if ((size_t)ctx->lds_limit < kAdaResolveLds + 4096) return hipSuccess;    // the adaptive calls then report an error
     return hipFuncSetAttribute((const void*)ada_resolve_kernel,

@@ -32,7 +32,6 @@ int check_config(const curdkv_config* cfg) {
     if (cfg->max_tokens > 0x7FFFFFFFLL) return CURDKV_ERR_UNSUPPORTED;   // indices are int32
     if (cfg->score_source < CURDKV_SCORE_KV || cfg->score_source > CURDKV_SCORE_VALUE) return CURDKV_ERR_INVALID_ARG;
     if (cfg->no_projection != 0 && cfg->no_projection != 1) return CURDKV_ERR_INVALID_ARG;
-    if (cfg->no_projection && cfg->dtype != CURDKV_DTYPE_BF16) return CURDKV_ERR_UNSUPPORTED;
     return CURDKV_OK;
 }
 

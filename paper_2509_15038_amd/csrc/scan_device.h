@@ -263,7 +263,7 @@ struct SketchF32 {
     float4 g[IN_REGS ? CB : 1][8];
 };
 
-template <int CB, bool IN_REGS, int SRC = kSrcKV>
+template <int CB, bool IN_REGS, int SRC = kSrcKV, bool PROJ = true>
 __device__ __forceinline__ float scan_tiles_f32(const SketchF32<CB, IN_REGS>& G, const float4* __restrict__ gs,
                                                 const float4* __restrict__ Kh, const float4* __restrict__ Vh,
                                                 int32_t n, int32_t t_begin, int32_t t_end, float* lds_rows,
@@ -297,8 +297,21 @@ __device__ __forceinline__ float scan_tiles_f32(const SketchF32<CB, IN_REGS>& G,
             // here, or the compiler lifts all of the loads out of the walk and runs out of registers
             int gl = lane;
             if (!IN_REGS) asm volatile("" : "+v"(gl));
+            if (!PROJ) {                        // squared norm of the stored row: 32 of its 128 floats per lane
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
+                for (int s = 0; s < 8; ++s) {
+                    if (SRC != kSrcV) {
+                        const float4 x = r.k[t2][s];
+                        lk = fmaf(x.x, x.x, lk); lk = fmaf(x.y, x.y, lk); lk = fmaf(x.z, x.z, lk); lk = fmaf(x.w, x.w, lk);
+                    }
+                    if (SRC != kSrcK) {
+                        const float4 x = r.v[t2][s];
+                        lv = fmaf(x.x, x.x, lv); lv = fmaf(x.y, x.y, lv); lv = fmaf(x.z, x.z, lv); lv = fmaf(x.w, x.w, lv);
+                    }
+                }
+            }
+#pragma unroll
+            for (int cb = 0; cb < (PROJ ? CB : 0); ++cb) {
                 f32x4 ak = f32x4{0.f, 0.f, 0.f, 0.f}, av = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < 8; ++s) {

@@ -92,12 +92,12 @@ template <int CB> struct StageF32 {
     static constexpr int kTiles = CB > 4 ? 128 : 256;     // 64 KB beside a 64 KB sketch, else 128 KB
 };
 
-template <int CB, int SRC>
+template <int CB, int SRC, bool PROJ>
 __global__ __launch_bounds__(256, 1) void scores_f32_kernel(
     const float4* __restrict__ K, const float4* __restrict__ V, const float4* __restrict__ Gp,
     float* __restrict__ scores, float* __restrict__ partial, int64_t n, int blocks_per_head,
     int64_t out_stride, int64_t out_offset, double* __restrict__ sums, int restart) {
-    constexpr bool kInRegs = CB <= 4;
+    constexpr bool kInRegs = CB <= 4;             // (PROJ = false comes with CB = 2 and never touches the sketch)
     constexpr int kStageTiles = StageF32<CB>::kTiles;
     __shared__ float stage[4][kStageTiles * kTileTokens];
     __shared__ float4 gs[kInRegs ? 1 : CB * 8 * 64];
@@ -107,7 +107,8 @@ __global__ __launch_bounds__(256, 1) void scores_f32_kernel(
 
     const float4* Gh = Gp + (size_t)head * (CB * 8 * 64);
     SketchF32<CB, kInRegs> G;
-    if (kInRegs) {
+    if (!PROJ) {
+    } else if (kInRegs) {
 #pragma unroll
         for (int cb = 0; cb < (kInRegs ? CB : 1); ++cb)
 #pragma unroll
@@ -132,8 +133,8 @@ __global__ __launch_bounds__(256, 1) void scores_f32_kernel(
     for (int32_t seg = t_begin; seg < t_end; seg += kStageTiles) {
         const int32_t seg_end = seg + kStageTiles < t_end ? seg + kStageTiles : t_end;
         const int32_t r0 = seg * kTileTokens;
-        acc_sum += scan_tiles_f32<CB, kInRegs, SRC>(G, gs, Kh, Vh, n32, seg, seg_end, mine, r0, lane,
-                                                    scan_phase(head, blk * 4 + wave));
+        acc_sum += scan_tiles_f32<CB, kInRegs, SRC, PROJ>(G, gs, Kh, Vh, n32, seg, seg_end, mine, r0, lane,
+                                                          scan_phase(head, blk * 4 + wave));
         const int32_t r1 = seg_end * kTileTokens < n32 ? seg_end * kTileTokens : n32;
         for (int32_t r = r0 + lane; r < r1; r += 64) __builtin_nontemporal_store(mine[r - r0], &sh[r]);
     }
@@ -211,7 +212,7 @@ static int pick_blocks_per_head(const curdkv_ctx* ctx, int64_t n) {
     const int64_t tiles = (n + kTileTokens - 1) / kTileTokens;
     const bool wide = ctx->cfg.dtype == CURDKV_DTYPE_BF16 && ctx->col_blocks > 2 && !ctx->cfg.no_projection;
     const bool f32 = ctx->cfg.dtype == CURDKV_DTYPE_F32;         // one workgroup per compute unit, like the wide kernel
-    const int64_t stage = f32 ? (ctx->col_blocks > 2 ? StageF32<8>::kTiles : StageF32<4>::kTiles)
+    const int64_t stage = f32 ? (ctx->col_blocks > 2 && !ctx->cfg.no_projection ? StageF32<8>::kTiles : StageF32<4>::kTiles)
                               : (wide ? Stage<8>::kTiles : Stage<4>::kTiles);
     const int64_t slots = (int64_t)ctx->num_cu * ((wide || f32 || ctx->heads <= ctx->num_cu) ? 1 : 2);
     int64_t cap = (tiles + 3) / 4;                                     // at least one tile per wave
@@ -278,18 +279,22 @@ hipError_t launch_scores(const curdkv_ctx* ctx, const void* K, const void* V, in
     } else {
         const float4* k = (const float4*)K; const float4* v = (const float4*)V; const float4* g = (const float4*)ctx->d_G;
         float* part = ctx->d_partial;
-#define CURDKV_LAUNCH(CBV, SRCV) \
-    scores_f32_kernel<CBV, SRCV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset, sums, rs)
-#define CURDKV_BY_SRC(CBV)                                                          \
+#define CURDKV_LAUNCH(CBV, SRCV, PROJV) \
+    scores_f32_kernel<CBV, SRCV, PROJV><<<grid, block, 0, stream>>>(k, v, g, scores, part, n, bph, out_stride, out_offset, sums, rs)
+#define CURDKV_BY_SRC(CBV, PROJV)                                                   \
     switch (ctx->cfg.score_source) {                                                \
-        case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK); break;                    \
-        case CURDKV_SCORE_VALUE: CURDKV_LAUNCH(CBV, kSrcV); break;                  \
-        default: CURDKV_LAUNCH(CBV, kSrcKV); break;                                 \
+        case CURDKV_SCORE_KEY: CURDKV_LAUNCH(CBV, kSrcK, PROJV); break;             \
+        case CURDKV_SCORE_VALUE: CURDKV_LAUNCH(CBV, kSrcV, PROJV); break;           \
+        default: CURDKV_LAUNCH(CBV, kSrcKV, PROJV); break;                          \
     }
-        switch (ctx->col_blocks) {       // 16-column MFMA blocks = 2 per 32 padded columns
-            case 1: CURDKV_BY_SRC(2) break;
-            case 2: CURDKV_BY_SRC(4) break;
-            default: CURDKV_BY_SRC(8) break;
+        if (ctx->cfg.no_projection) {
+            CURDKV_BY_SRC(2, false)
+        } else {
+            switch (ctx->col_blocks) {   // 16-column MFMA blocks = 2 per 32 padded columns
+                case 1: CURDKV_BY_SRC(2, true) break;
+                case 2: CURDKV_BY_SRC(4, true) break;
+                default: CURDKV_BY_SRC(8, true) break;
+            }
         }
 #undef CURDKV_BY_SRC
 #undef CURDKV_LAUNCH
