@@ -132,15 +132,17 @@ class Context:
         self.cfg = make_config(layers, kv_heads, group_size, head_dim, sketch_dim, dtype,
                                max_tokens, seed, source, projection)
         self._h = C.c_void_p()
+        self._destroy = lib().curdkv_destroy        # kept here: module globals may be gone at interpreter exit
         rc = lib().curdkv_create(C.byref(self._h), C.byref(self.cfg))
         if rc != OK:
-            self._h = C.c_void_p()
+            self._h = None
             raise CurdkvError(rc, "curdkv_create")
 
     def close(self):
-        if getattr(self, "_h", None) and self._h.value:
-            lib().curdkv_destroy(self._h)
-            self._h = C.c_void_p()
+        h = getattr(self, "_h", None)
+        if h is not None and h.value:
+            self._h = None
+            self._destroy(h)
 
     __del__ = close
 
