@@ -306,6 +306,42 @@ def test_adaptive_budgets_many_heads(gu, H, n):
         _ada_case(gu, sc, k, s, alpha)
 
 
+def test_adaptive_budgets_random_distributions(gu):
+    # Seeded sweep over shapes and score distributions: continuous, heavily tied (multiples of
+    # 1/8), a wide range with scores of 2 and above (the last bin), nine tenths of a head equal
+    # (a bin too full for the lists), and strongly skewed.  Given scores: exact.  Both the
+    # allocating entry point and the one on the static workspace.
+    import torch
+    rng = np.random.default_rng(20250915)
+    for case in range(60):
+        L = int(rng.integers(1, 10)); H = int(rng.choice([1, 2, 3, 8, 16, 40, 100])); n = int(rng.integers(2, 3000))
+        if case % 10 == 0:
+            L, H, n = int(rng.integers(1, 4)), int(rng.choice([2, 8])), int(rng.integers(20000, 70000))
+        kind = case % 5
+        x = rng.random((L, H, n))
+        if kind == 0: sc = x
+        elif kind == 1: sc = np.round(x * 8) / 8
+        elif kind == 2: sc = np.exp(rng.normal(0, 3, (L, H, n)))
+        elif kind == 3: sc = np.where(x < 0.9, 0.25, x)
+        else: sc = x ** 8
+        sc = sc.astype(np.float32) if kind == 2 else (sc / sc.sum(-1, keepdims=True)).astype(np.float32)
+        s = int(rng.choice([0, 1, 4, 64])); k = int(rng.integers(0, n + 1))
+        alpha = float(rng.choice([0.0, 0.1, 0.2, 0.5, 0.9, 1.0]))
+        print(f"  case {case}: L{L} H{H} n{n} kind{kind} k{k} s{s} alpha{alpha}", flush=True)
+        with B.Context(L, H, 4, 128, 64, "bf16", n, 1) as ctx:
+            d = torch.from_numpy(sc).cuda()
+            out = torch.full((L * H,), -1, dtype=torch.int32, device="cuda")
+            out2 = torch.full((L * H,), -1, dtype=torch.int32, device="cuda")
+            ctx.adaptive_budgets(d, n, k, s, alpha, out)
+            ctx.adaptive_budgets_noalloc(d, n, k, s, alpha, out2)
+            torch.cuda.synchronize()
+            assert torch.equal(out, out2)
+            got = out.cpu().numpy().reshape(L, H)
+        for l in range(L):
+            want = orc.adaptive_budgets(sc[l].astype(np.float64), k, s, alpha)
+            assert got[l].tolist() == want.tolist(), (case, l)
+
+
 def test_adaptive_budgets_general_routes(gu):
     # inputs that the usual route of the allocation hands to its general one: a layer whose
     # scores are (nearly) all equal, so that the bin holding the threshold is too full for
