@@ -574,14 +574,16 @@ def test_incremental_scoring_matches_full_cache(gu, dtype):
 
 def test_random_small_shapes_both_paths(gu):
     rng = np.random.default_rng(2024)
-    for case in range(24):
-        L = int(rng.integers(1, 4)); H = int(rng.choice([1, 2, 3, 8])); n = int(rng.integers(1, 700))
+    for case in range(36):
+        L = int(rng.integers(1, 4)); H = int(rng.choice([1, 2, 3, 8])); n = int(rng.integers(1, 700 if case < 24 else 5000))
         r = int(rng.choice([8, 20, 32, 64, 128])); s = int(rng.choice([0, 1, 4, 9]))
         dtype = "bf16" if case % 4 else "fp32"
         cfg = wl.scaled(wl.CONFIGS["c2"], layers=L, kv_heads=H, n=n, r=r, dtype=dtype)
         b = rng.integers(0, n + 1, size=L * H).astype(np.int32)
-        print(f"  case {case}: L{L} H{H} n{n} r{r} s{s} {dtype}", flush=True)
-        gu.run_and_check(cfg, b, n_sink=s, one_call=bool(case % 2))
+        source = ["kv", "kv", "k", "v"][case % 4 if case >= 12 else 0]
+        projection = not (case >= 12 and case % 3 == 0)
+        print(f"  case {case}: L{L} H{H} n{n} r{r} s{s} {dtype} {source} projection={projection}", flush=True)
+        gu.run_and_check(cfg, b, n_sink=s, one_call=bool(case % 2), source=source, projection=projection)
     for case in range(6):                                  # enough heads for the fused kernel
         n = int(rng.integers(1, 400)); r = int(rng.choice([20, 32, 64])); s = int(rng.choice([0, 4, 50]))
         cfg = wl.scaled(wl.CONFIGS["c3"], n=n, r=r)
