@@ -34,6 +34,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, vendor figure
 FP32_MFMA_PEAK_TFLOPS = 157.3     # MI355X, dense fp32 matrix rate
+FUSED_GATHER_MAX_PERCENT = 11     # curdkv_compress: above this share of rows kept, the fused kernel only scores
 
 
 def algorithmic_bytes(cfg, budgets, source="kv"):
@@ -320,7 +321,7 @@ def main():
     ctx = B.Context(L, H, cfg.group, d, cfg.r, cfg.dtype, n, cfg.sketch_seed, args.source,
                     not args.no_projection)
     s = cfg.n_sink
-    fused = ctx.uses_fused_kernel(n) and total * 4 <= heads * n
+    fused = ctx.uses_fused_kernel(n) and total * 100 <= heads * n * FUSED_GATHER_MAX_PERCENT
     timer = Timer(args.steps, args.warmup)
 
     if args.copy_calibration:
@@ -390,14 +391,14 @@ def main():
             b = wl.budgets_for(cfg, kp)
             o, c3, a = time_compress(ctx, timer, Kd, Vd, cfg, b, bufs)
             more[f"c3 keep={kp:g}"] = dict(summary(o, a), three_calls_ms=c3["ms_per_step"],
-                                           traffic=measured_traffic("c3", kp, ctx.uses_fused_kernel(n) and int(b.sum()) * 4 <= heads * n, heads)[0])
+                                           traffic=measured_traffic("c3", kp, ctx.uses_fused_kernel(n) and int(b.sum()) * 100 <= heads * n * FUSED_GATHER_MAX_PERCENT, heads)[0])
         c4 = wl.CONFIGS["c4"]
         K4, V4 = wl.device_cache(c4)
         b4 = wl.budgets_for(c4)
         with B.Context(c4.layers, c4.kv_heads, c4.group, c4.d, c4.r, c4.dtype, c4.n, c4.sketch_seed) as ctx4:
             o, c3, a = time_compress(ctx4, timer, K4, V4, c4, b4, bufs)
             more[f"c4 keep={c4.keep[0]:g}"] = dict(summary(o, a), three_calls_ms=c3["ms_per_step"],
-                                                   traffic=measured_traffic("c4", c4.keep[0], True, heads)[0])
+                                                   traffic=measured_traffic("c4", c4.keep[0], ctx4.uses_fused_kernel(c4.n) and int(b4.sum()) * 100 <= heads * c4.n * FUSED_GATHER_MAX_PERCENT, heads)[0])
         # (nothing is freed between the timed sections: the driver wipes freed device memory in
         # the background, and for some hundred milliseconds after a free of several GiB every
         # kernel here runs 3 to 4 % slower)

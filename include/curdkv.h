@@ -158,8 +158,9 @@ int curdkv_compact(curdkv_ctx* ctx, const void* K, const void* V, int64_t n,
  * library then uses a scratch buffer it allocates on first need).  Where
  * curdkv_uses_fused_kernel says so, one fused kernel does everything with one
  * workgroup per (layer, group) and the scores never pass through HBM between
- * the steps (when more than 25 % of all rows are kept, only its scoring phases
- * are used and the stand-alone selection and gather kernels follow); otherwise
+ * the steps (when more than 11 % of all rows are kept, only its scoring phases
+ * are used and the stand-alone selection and gather kernels follow: the gather
+ * kernel moves rows faster than the fused kernel's last phase); otherwise
  * the kernels of the separate calls are launched.  The normalising sum is taken
  * in a different order in the two cases, so scores can differ in the last bits
  * between them. */

@@ -322,11 +322,15 @@ int curdkv_compress(curdkv_ctx* ctx, const void* K, const void* V, int64_t n, co
     const int rc = sync_offsets(ctx, offsets, budgets, n, st, &total);
     if (rc != CURDKV_OK) return rc;
     if (total > 0 && (!indices || !K_out || !V_out)) return CURDKV_ERR_INVALID_ARG;
-    // One kernel for everything when it applies -- unless more than a quarter of the rows are
-    // kept: the gather then dominates and the stand-alone gather kernel (four times the
-    // threads per CU) moves rows a little faster than the fused kernel's last phase.
+    // One kernel for everything when it applies and about a tenth of the rows or fewer are kept.
+    // Beyond, the stand-alone gather kernel (many small workgroups, 32 waves per compute unit)
+    // moves rows enough faster than the fused kernel's last phase (one long-lived workgroup of 8
+    // waves per unit) to pay for two more launches.  Measured at 256 heads of 32768 tokens, one
+    // call at keep 5 / 8 / 10 / 12 / 20 / 30 %: fused 783 / 832 / 863 / 897 / 1029 / 1195 us,
+    // scoring phases + selection kernel + gather kernel 792 / 832 / 859 / 887 / 993 / 1125 us:
+    // level at a tenth (the paper's strongest compression), 4 to 6 % apart from a fifth on.
     const bool fusable = fused_applicable(ctx, n);
-    const bool big_gather = total * 4 > (int64_t)ctx->heads * n;
+    const bool big_gather = total * 100 > (int64_t)ctx->heads * n * kFusedGatherMaxPercent;
     if (fusable && !big_gather)
         return launch_fused(ctx, K, V, n, n_sink, ctx->plan.d_offsets, scores, indices, K_out, V_out, st) == hipSuccess
                    ? CURDKV_OK : CURDKV_ERR_HIP;

@@ -15,7 +15,8 @@ constexpr int kColBlock = 32;          // sketch columns per MFMA tile (M of the
 constexpr int kMaxColBlocks = 4;       // r padded to 32, 64 or 128
 constexpr int kMaxBlocksPerHead = 64;  // partial sums kept per (layer, group)
 constexpr int kTileTokens = 32;        // tokens per wave tile
-constexpr int kCompactRowsPerBlock = 128;  // output rows one gather block copies
+constexpr int kCompactRowsPerBlock = 128;  // output rows per entry of the gather's table of heads
+constexpr int kFusedGatherMaxPercent = 11;  // curdkv_compress: share of rows kept up to which the fused kernel also gathers
 
 struct BlockInfo {                     // for gather block b, whose first output row is b*128:
     int64_t head_end;                  //   offsets[head + 1]

@@ -101,32 +101,31 @@ __global__ __launch_bounds__(kFusedThreads, 2) void fused_kernel(
     for (int32_t p = tid; p < k; p += kFusedThreads) out[p] = stage[p];
 
     // ---- 5. gather ---------------------------------------------------------------------
+    // The head's K rows first, then its V rows: one source and one destination stream at a
+    // time (a plain copy kernel is some 8 % faster on one array than on two interleaved, and
+    // this order measured 0.3-0.5 % on the whole kernel), 16 rows in flight per thread.
     constexpr int kRowsPerIter = kFusedThreads / 16;      // 32 rows per instruction
-    constexpr int kIters = 8;
+    constexpr int kIters = 16;
     const int c = tid & 15, rsub = tid >> 4;
-    const u32x4* Kr = reinterpret_cast<const u32x4*>(Kh);
-    const u32x4* Vr = reinterpret_cast<const u32x4*>(Vh);
-    u32x4* Ko = K_out + (size_t)o0 * 16;
-    u32x4* Vo = V_out + (size_t)o0 * 16;
-    for (int32_t p0 = 0; p0 < k; p0 += kRowsPerIter * kIters) {
-        int32_t idx[kIters];
+#pragma unroll 1
+    for (int which = 0; which < 2; ++which) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(which ? Vh : Kh);
+        u32x4* dst = (which ? V_out : K_out) + (size_t)o0 * 16;
+#pragma unroll 1
+        for (int32_t p0 = 0; p0 < k; p0 += kRowsPerIter * kIters) {
+            int32_t idx[kIters];
 #pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int32_t p = p0 + it * kRowsPerIter + rsub;
-            idx[it] = stage[p < k ? p : k - 1];
-        }
-        u32x4 vk[kIters], vv[kIters];
+            for (int it = 0; it < kIters; ++it) {
+                const int32_t p = p0 + it * kRowsPerIter + rsub;
+                idx[it] = stage[p < k ? p : k - 1];
+            }
+            u32x4 v[kIters];
 #pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            vk[it] = __builtin_nontemporal_load(Kr + (size_t)idx[it] * 16 + c);
-            vv[it] = __builtin_nontemporal_load(Vr + (size_t)idx[it] * 16 + c);
-        }
+            for (int it = 0; it < kIters; ++it) v[it] = __builtin_nontemporal_load(src + (size_t)idx[it] * 16 + c);
 #pragma unroll
-        for (int it = 0; it < kIters; ++it) {
-            const int32_t p = p0 + it * kRowsPerIter + rsub;
-            if (p < k) {
-                __builtin_nontemporal_store(vk[it], Ko + (size_t)p * 16 + c);
-                __builtin_nontemporal_store(vv[it], Vo + (size_t)p * 16 + c);
+            for (int it = 0; it < kIters; ++it) {
+                const int32_t p = p0 + it * kRowsPerIter + rsub;
+                if (p < k) __builtin_nontemporal_store(v[it], dst + (size_t)p * 16 + c);
             }
         }
     }
